@@ -1,0 +1,392 @@
+"""CPU oracle for the Token Recycling decode step.  TEST INFRASTRUCTURE ONLY.
+
+Plain, slow numpy written from the paper; it shares no code with the HIP path and
+imports nothing from it.  Only tests, the smoke check and the benchmark's
+`cpu_baseline` leg may call it; the product path never does.
+
+What follows the paper, function by function
+  build_tree      Section 3.2 worked example and Algorithm 1 (static-tree BFS)
+  topk_ids        Section 2.1, argtopk with x^0 = argmax; ties to the smallest
+                  index (Appendix A.1)
+  accept          Section 2.2 "Guess and Verify" (chain rule) applied to every
+                  root-to-node path; the longest correct sequence wins (Section 3.3)
+  update_matrix   Section 3.3, M[x_i] = argtopk(p_{i+1}) for every node of S,
+                  duplicates resolved as in Appendix A.5 ("Last" by default)
+  forward_nodes   Section 2.2 equations: node i sees P(x | s, its ancestors), i.e.
+                  tree attention (Section 2.2 "Tree Attention")
+  tr_step / tr_generate / ar_generate   the decode loop of Sections 2.1 and 3
+
+The paper runs unmodified HuggingFace Llama-family models and does not restate the
+architecture.  The transformer here is the public Llama description: pre-RMSNorm
+(eps 1e-5), rotary embedding with base 10000 and half-split pairing (i, i+hd/2),
+grouped-query attention scaled by 1/sqrt(hd), SwiGLU down(silu(gate)*up), final
+RMSNorm, untied LM head, no biases.  Masked positions are excluded exactly (the
+paper's additive-mask leakage, Appendix A.1, is an artefact and is not reproduced).
+
+Readings taken where the paper is silent or garbled
+  * Algorithm 1 never advances d and gathers once more than needed: d is advanced
+    and the last gather skipped.
+  * depth = number of tree layers including the root; a step confirms 1..depth tokens.
+  * duplicates in S update M last-wins (one of the outcomes the paper allows).
+  * duplicate tokens among siblings both "match"; winner = deepest fully matched
+    node, then smallest breadth-first index.
+  * prefill covers prompt[0..P-2]; the last prompt token is the first root; prefill
+    does not touch M.
+  * tree node n sits at position L + depth(n).
+
+Precision: `dtype` is float64 by default (weights are float32 / bf16-representable
+values, converted on use); float32 is available for large shapes.
+
+Pins (tests/test_oracle_*.py): worked examples of Sections 2.2, 3.2 and Appendix A.5,
+brute force over explicit paths, per-path causal attention, an independent Llama
+forward (HuggingFace `LlamaForCausalLM`) on a chain, full sort for top-k, and
+losslessness against plain greedy decoding.  MAT / speed-up values are parity
+unpinned (they need the paper's datasets and trained weights).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------
+# tree template (Section 3.2; Appendix A.2)
+# ----------------------------------------------------------------------------
+@dataclass
+class Tree:
+    parent: np.ndarray          # [N] int, parent[0] = -1
+    rank: np.ndarray            # [N] int, column of M[token(parent)], rank[0] = -1
+    depth: np.ndarray           # [N] int, root = 0
+    paths: List[List[int]]      # paths[n] = node indices root..n
+    n_layers: int               # number of layers including the root layer
+
+    @property
+    def n_nodes(self) -> int:
+        return len(self.parent)
+
+
+def make_tree(parent: Sequence[int], rank: Sequence[int], k: int) -> Tree:
+    """Derive depths and root-to-node paths; check breadth-first order."""
+    parent = np.asarray(parent, dtype=np.int64)
+    rank = np.asarray(rank, dtype=np.int64)
+    n = len(parent)
+    if n < 1 or parent[0] != -1:
+        raise ValueError("node 0 must be the root")
+    depth = np.zeros(n, dtype=np.int64)
+    paths: List[List[int]] = [[0]]
+    seen = set()
+    for i in range(1, n):
+        p = int(parent[i])
+        if not (0 <= p < i):
+            raise ValueError("parent must precede child")
+        if not (0 <= rank[i] < k):
+            raise ValueError("rank out of range")
+        if (p, int(rank[i])) in seen:
+            raise ValueError("duplicate (parent, rank)")
+        seen.add((p, int(rank[i])))
+        depth[i] = depth[p] + 1
+        if depth[i] < depth[i - 1]:
+            raise ValueError("nodes must be in layer order")
+        paths.append(paths[p] + [i])
+    return Tree(parent, rank, depth, paths, int(depth.max()) + 1)
+
+
+def build_tree(M: np.ndarray, tree: Tree, root: int) -> np.ndarray:
+    """Merged sequence S (Algorithm 1): layer by layer, every node takes the
+    rank[n]-th candidate stored for its parent's token."""
+    S = np.zeros(tree.n_nodes, dtype=np.int64)
+    S[0] = root
+    layer = [0]
+    for d in range(1, tree.n_layers):
+        xs = {n: M[S[n]] for n in layer}                 # "get all candidates of L from M"
+        nxt = [n for n in range(tree.n_nodes) if tree.depth[n] == d]
+        for n in nxt:                                    # "extract next layer tokens with Tree"
+            S[n] = xs[int(tree.parent[n])][tree.rank[n]]
+        layer = nxt
+    return S
+
+
+# ----------------------------------------------------------------------------
+# candidates, acceptance, update (Sections 2.1, 2.2, 3.3; Appendix A.5)
+# ----------------------------------------------------------------------------
+def topk_ids(p: np.ndarray, k: int) -> np.ndarray:
+    """Indices of the k largest entries, most probable first; equal values keep the
+    smaller index first (so column 0 is argmax with the smallest-index tie rule)."""
+    return np.argsort(-np.asarray(p), kind="stable")[:k].astype(np.int64)
+
+
+@dataclass
+class Accept:
+    n_accepted: int            # a: matched draft tokens (0..depth-1)
+    winner: int                # node whose output is the bonus token
+    path: List[int]            # node indices root..winner (a + 1 entries)
+    emitted: List[int]         # a matched draft tokens followed by the bonus token
+    bonus: int
+
+
+def accept(S: np.ndarray, out: np.ndarray, tree: Tree) -> Accept:
+    """Guess-and-verify on every root-to-node path: node n is correct when each draft
+    token on its path equals the model output at that token's parent."""
+    best = 0
+    for n in range(tree.n_nodes):
+        path = tree.paths[n]
+        good = all(S[path[i]] == out[path[i - 1]] for i in range(1, len(path)))
+        if good and tree.depth[n] > tree.depth[best]:
+            best = n                                     # deepest, then smallest index
+    path = tree.paths[best]
+    emitted = [int(S[i]) for i in path[1:]] + [int(out[best])]
+    return Accept(len(path) - 1, best, list(path), emitted, int(out[best]))
+
+
+def update_matrix(M: np.ndarray, S: np.ndarray, topk: np.ndarray, mode: str = "last",
+                  nodes: Optional[Sequence[int]] = None) -> None:
+    """M[S[n]] = topk[n] for every node (accepted, rejected and the root).
+    mode "last": a token that occurs several times keeps its last occurrence's
+    candidates; "first": its first occurrence's.  `nodes` restricts the update
+    (e.g. to the accepted path, the ablation of Section 5.2)."""
+    order = list(range(len(S))) if nodes is None else list(nodes)
+    if mode == "last":
+        for n in order:
+            M[S[n]] = topk[n]
+    elif mode == "first":
+        done = set()
+        for n in order:
+            if int(S[n]) not in done:
+                M[S[n]] = topk[n]
+                done.add(int(S[n]))
+    else:
+        raise ValueError(mode)
+
+
+# ----------------------------------------------------------------------------
+# transformer (public Llama architecture; see module docstring)
+# ----------------------------------------------------------------------------
+@dataclass
+class Config:
+    n_layers: int
+    d_model: int
+    n_heads: int
+    n_kv_heads: int
+    head_dim: int
+    d_ffn: int
+    vocab: int
+    rms_eps: float = 1e-5
+    rope_theta: float = 10000.0
+
+
+class KVCache:
+    """k[l], v[l]: [capacity, n_kv_heads, head_dim]; rows 0..len-1 are committed."""
+
+    def __init__(self, cfg: Config, capacity: int, dtype=np.float64):
+        self.k = [np.zeros((capacity, cfg.n_kv_heads, cfg.head_dim), dtype) for _ in range(cfg.n_layers)]
+        self.v = [np.zeros((capacity, cfg.n_kv_heads, cfg.head_dim), dtype) for _ in range(cfg.n_layers)]
+        self.len = 0
+        self.capacity = capacity
+
+
+def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
+    return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps) * g
+
+
+def rope(x: np.ndarray, pos: int, theta: float) -> np.ndarray:
+    """x: [heads, hd].  Pair (i, i + hd/2) is rotated by pos * theta**(-2i/hd)."""
+    hd = x.shape[-1]
+    half = hd // 2
+    ang = pos * theta ** (-2.0 * np.arange(half, dtype=np.float64) / hd)
+    c, s = np.cos(ang).astype(x.dtype), np.sin(ang).astype(x.dtype)
+    a, b = x[..., :half], x[..., half:]
+    return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
+
+
+def silu(x: np.ndarray) -> np.ndarray:
+    return x / (1.0 + np.exp(-x))
+
+
+def _attend(q: np.ndarray, K: np.ndarray, V: np.ndarray, group: int) -> np.ndarray:
+    """q: [H, hd]; K, V: [T, Hkv, hd] — the keys this query may see, nothing else.
+    Softmax over exactly those T keys, scale 1/sqrt(hd); query head h uses KV head
+    h // group."""
+    H, hd = q.shape
+    qg = q.reshape(H // group, group, hd)
+    s = np.einsum("tkd,kgd->kgt", K, qg) / np.sqrt(hd)
+    s = s - s.max(axis=-1, keepdims=True)
+    p = np.exp(s)
+    p = p / p.sum(axis=-1, keepdims=True)
+    return np.einsum("kgt,tkd->kgd", p, V).reshape(H, hd)
+
+
+def _attend_batched(Q: np.ndarray, Kp: np.ndarray, Vp: np.ndarray, K: np.ndarray, V: np.ndarray,
+                    paths: Sequence[Sequence[int]], group: int) -> np.ndarray:
+    """Same result as `_attend` per node, with the prefix part done as matrix products
+    for all nodes at once.  Q: [N, H, hd]; Kp, Vp: [L, Hkv, hd]; K, V: [N, Hkv, hd]."""
+    N, H, hd = Q.shape
+    Hkv = H // group
+    L = Kp.shape[0]
+    Qg = Q.reshape(N, Hkv, group, hd)
+    Qm = Qg.transpose(1, 0, 2, 3).reshape(Hkv, N * group, hd)
+    sp = np.matmul(Qm, np.ascontiguousarray(Kp.transpose(1, 2, 0)))        # [Hkv, N*g, L]
+    sp = sp.reshape(Hkv, N, group, L).transpose(1, 0, 2, 3) / np.sqrt(hd)  # [N, Hkv, g, L]
+    Pp = np.empty((N, Hkv, group, L), Q.dtype)
+    out = np.empty((N, Hkv, group, hd), Q.dtype)
+    for n in range(N):
+        idx = list(paths[n])
+        st = np.einsum("tkd,kgd->kgt", K[idx], Qg[n]) / np.sqrt(hd)        # [Hkv, g, |path|]
+        m = np.maximum(sp[n].max(axis=-1), st.max(axis=-1))[..., None] if L else st.max(axis=-1)[..., None]
+        ep, et = np.exp(sp[n] - m), np.exp(st - m)
+        z = ep.sum(axis=-1, keepdims=True) + et.sum(axis=-1, keepdims=True)
+        Pp[n] = ep / z
+        out[n] = np.einsum("kgt,tkd->kgd", et / z, V[idx])
+    Pm = Pp.transpose(1, 0, 2, 3).reshape(Hkv, N * group, L)
+    op = np.matmul(Pm, np.ascontiguousarray(Vp.transpose(1, 0, 2)))        # [Hkv, N*g, hd]
+    out += op.reshape(Hkv, N, group, hd).transpose(1, 0, 2, 3)
+    return out.reshape(N, H, hd)
+
+
+def forward_nodes(cfg: Config, w: dict, kv: KVCache, tokens: Sequence[int], pos: Sequence[int],
+                  paths: Sequence[Sequence[int]], dtype=np.float64, row_independent: bool = False,
+                  want_logits: bool = True):
+    """One forward over N nodes that all follow the committed prefix kv[0..len-1].
+
+    Node n is at position pos[n] and attends to the whole prefix plus the nodes listed
+    in paths[n] (its ancestors and itself, root first).  Returns (logits [N, V],
+    node_k, node_v) with node_k[l], node_v[l]: [N, Hkv, hd]; the cache is not modified.
+
+    row_independent=True computes every node with vector operations only, so a node's
+    result does not depend on which other nodes share the pass (same operation shapes
+    as decoding that token alone)."""
+    N, L = len(tokens), kv.len
+    H, Hkv, hd = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+    group = H // Hkv
+    X = np.stack([w["embed"][t].astype(dtype) for t in tokens])          # [N, d]
+    node_k, node_v = [], []
+
+    def lin(Wm: np.ndarray, A: np.ndarray) -> np.ndarray:
+        Wd = Wm.astype(dtype, copy=False)
+        if row_independent:
+            return np.stack([Wd @ A[n] for n in range(A.shape[0])])
+        return A @ Wd.T
+
+    for l in range(cfg.n_layers):
+        lw = w["layers"][l]
+        Hn = rmsnorm(X, lw["attn_norm"].astype(dtype), cfg.rms_eps)
+        Q = lin(lw["wq"], Hn).reshape(N, H, hd)
+        K = lin(lw["wk"], Hn).reshape(N, Hkv, hd)
+        V = lin(lw["wv"], Hn).reshape(N, Hkv, hd)
+        for n in range(N):
+            Q[n] = rope(Q[n], pos[n], cfg.rope_theta)
+            K[n] = rope(K[n], pos[n], cfg.rope_theta)
+        Kp = kv.k[l][:L].astype(dtype, copy=False)
+        Vp = kv.v[l][:L].astype(dtype, copy=False)
+        if row_independent:
+            A = np.empty((N, H, hd), dtype)
+            for n in range(N):
+                idx = list(paths[n])
+                A[n] = _attend(Q[n], np.concatenate([Kp, K[idx]], axis=0),
+                               np.concatenate([Vp, V[idx]], axis=0), group)
+        else:
+            A = _attend_batched(Q, Kp, Vp, K, V, paths, group)
+        X = X + lin(lw["wo"], A.reshape(N, H * hd))
+        Hn = rmsnorm(X, lw["ffn_norm"].astype(dtype), cfg.rms_eps)
+        X = X + lin(lw["w_down"], silu(lin(lw["w_gate"], Hn)) * lin(lw["w_up"], Hn))
+        node_k.append(K)
+        node_v.append(V)
+    logits = None
+    if want_logits:
+        logits = lin(w["lm_head"], rmsnorm(X, w["final_norm"].astype(dtype), cfg.rms_eps))
+    return logits, node_k, node_v
+
+
+def commit(kv: KVCache, node_k, node_v, nodes: Sequence[int]) -> None:
+    """Append the listed nodes' keys/values, in order, after the committed prefix."""
+    L = kv.len
+    if L + len(nodes) > kv.capacity:
+        raise ValueError("KV capacity exceeded")
+    for l in range(len(kv.k)):
+        for i, n in enumerate(nodes):
+            kv.k[l][L + i] = node_k[l][n]
+            kv.v[l][L + i] = node_v[l][n]
+    kv.len = L + len(nodes)
+
+
+def prefill(cfg: Config, w: dict, kv: KVCache, tokens: Sequence[int], dtype=np.float64,
+            row_independent: bool = False, chunk: int = 64) -> None:
+    """Run `tokens` causally after the committed prefix and commit their keys/values."""
+    tokens = list(tokens)
+    for lo in range(0, len(tokens), chunk):
+        part = tokens[lo:lo + chunk]
+        n = len(part)
+        pos = [kv.len + i for i in range(n)]
+        paths = [list(range(i + 1)) for i in range(n)]                    # chain
+        _, nk, nv = forward_nodes(cfg, w, kv, part, pos, paths, dtype, row_independent,
+                                  want_logits=False)
+        commit(kv, nk, nv, list(range(n)))
+
+
+# ----------------------------------------------------------------------------
+# decode loops
+# ----------------------------------------------------------------------------
+@dataclass
+class StepResult:
+    S: np.ndarray
+    logits: np.ndarray
+    topk: np.ndarray
+    acc: Accept
+
+
+def integer_pipeline(M: np.ndarray, tree: Tree, S: np.ndarray, logits: np.ndarray, k: int,
+                     update_mode: str = "last", update_accepted_only: bool = False):
+    """Top-k, accept and matrix update from given logits (in place on M)."""
+    topk = np.stack([topk_ids(logits[n], k) for n in range(tree.n_nodes)])
+    acc = accept(S, topk[:, 0], tree)
+    update_matrix(M, S, topk, update_mode, acc.path if update_accepted_only else None)
+    return topk, acc
+
+
+def tr_step(cfg: Config, w: dict, kv: KVCache, M: np.ndarray, tree: Tree, root: int, k: int,
+            dtype=np.float64, row_independent: bool = False, update_mode: str = "last",
+            update_accepted_only: bool = False) -> StepResult:
+    """Draft (build_tree), verify (one forward), accept, update M, commit accepted K/V."""
+    S = build_tree(M, tree, root)
+    L = kv.len
+    pos = [L + int(d) for d in tree.depth]
+    logits, nk, nv = forward_nodes(cfg, w, kv, S, pos, tree.paths, dtype, row_independent)
+    topk, acc = integer_pipeline(M, tree, S, logits, k, update_mode, update_accepted_only)
+    commit(kv, nk, nv, acc.path)
+    return StepResult(S, logits, topk, acc)
+
+
+def tr_generate(cfg: Config, w: dict, M: np.ndarray, tree: Tree, prompt: Sequence[int],
+                n_new: int, k: int, capacity: Optional[int] = None, dtype=np.float64,
+                row_independent: bool = False, on_step=None):
+    """Prefill prompt[:-1], then repeat tr_step from root = prompt[-1] until n_new tokens
+    exist (overshoot truncated).  Returns (tokens, accepted_lengths, kv)."""
+    capacity = capacity or (len(prompt) + n_new + tree.n_nodes + tree.n_layers)
+    kv = KVCache(cfg, capacity, dtype)
+    prefill(cfg, w, kv, prompt[:-1], dtype, row_independent)
+    root, out, lens = int(prompt[-1]), [], []
+    while len(out) < n_new:
+        r = tr_step(cfg, w, kv, M, tree, root, k, dtype, row_independent)
+        out.extend(r.acc.emitted)
+        lens.append(r.acc.n_accepted + 1)
+        root = r.acc.bonus
+        if on_step is not None:
+            on_step(r)
+    return out[:n_new], lens, kv
+
+
+def ar_generate(cfg: Config, w: dict, prompt: Sequence[int], n_new: int,
+                capacity: Optional[int] = None, dtype=np.float64, row_independent: bool = False):
+    """Plain greedy decoding (Section 2.1): one token per forward, x = argmax p."""
+    capacity = capacity or (len(prompt) + n_new + 1)
+    kv = KVCache(cfg, capacity, dtype)
+    prefill(cfg, w, kv, prompt[:-1], dtype, row_independent)
+    tok, out, all_logits = int(prompt[-1]), [], []
+    for _ in range(n_new):
+        logits, nk, nv = forward_nodes(cfg, w, kv, [tok], [kv.len], [[0]], dtype, row_independent)
+        commit(kv, nk, nv, [0])
+        tok = int(topk_ids(logits[0], 1)[0])
+        out.append(tok)
+        all_logits.append(logits[0])
+    return out, all_logits, kv

@@ -1,0 +1,289 @@
+"""Seeded synthetic inputs for the Token Recycling decode step.
+
+This module only *produces data*: model shapes, random-init weights, prompts,
+the initial adjacency matrix and static tree templates.  It holds none of the
+method's arithmetic (no forward pass, no tree gather, no accept rule) and it
+imports neither the HIP binding nor the CPU oracle; tests and the benchmark
+hand its outputs to both sides.
+
+Stand-ins: the paper measures trained Vicuna / Code Llama checkpoints on
+SpecBench / MBPP prompts (Section 4.1).  Neither weights nor prompts are
+available offline, so weights are random-init at the same shapes and prompts
+are Zipf-distributed token ids with planted repeated n-grams (the redundancy
+the paper attributes to its workloads, Section 4.2).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Sequence, Tuple
+
+import numpy as np
+import torch
+
+
+# ----------------------------------------------------------------------------
+# model shapes
+# ----------------------------------------------------------------------------
+@dataclass(frozen=True)
+class ModelShape:
+    name: str
+    n_layers: int
+    d_model: int
+    n_heads: int
+    n_kv_heads: int
+    head_dim: int
+    d_ffn: int
+    vocab: int
+    dtype: str  # "f32" | "bf16"
+    rms_eps: float = 1e-5
+    rope_theta: float = 10000.0
+
+    def weight_params(self) -> int:
+        """Projection + LM-head parameters streamed once per step (no embedding)."""
+        d, hq, hk = self.d_model, self.n_heads * self.head_dim, self.n_kv_heads * self.head_dim
+        per_layer = d * hq + 2 * d * hk + hq * d + 3 * d * self.d_ffn
+        return self.n_layers * per_layer + self.vocab * d
+
+
+SHAPES: Dict[str, ModelShape] = {
+    # tiny fp32 config the CPU oracle finishes in seconds
+    "tiny": ModelShape("tiny", 2, 128, 4, 4, 32, 344, 1024, "f32"),
+    # tiny bf16 config with head_dim 128 (exercises the MFMA kernels at toy size)
+    "tiny_bf16": ModelShape("tiny_bf16", 2, 256, 2, 2, 128, 704, 2048, "bf16"),
+    "tiny_gqa_bf16": ModelShape("tiny_gqa_bf16", 2, 512, 4, 2, 128, 1376, 4096, "bf16"),
+    "7b": ModelShape("7b", 32, 4096, 32, 32, 128, 11008, 32000, "bf16"),
+    "13b": ModelShape("13b", 40, 5120, 40, 40, 128, 13824, 32000, "bf16"),
+    "70b": ModelShape("70b", 80, 8192, 64, 8, 128, 28672, 128256, "bf16"),
+}
+
+
+def with_layers(shape: ModelShape, n_layers: int) -> ModelShape:
+    """Same widths, fewer layers (full-width parity cases the oracle can afford)."""
+    return ModelShape(f"{shape.name}_l{n_layers}", n_layers, shape.d_model, shape.n_heads,
+                      shape.n_kv_heads, shape.head_dim, shape.d_ffn, shape.vocab, shape.dtype,
+                      shape.rms_eps, shape.rope_theta)
+
+
+# ----------------------------------------------------------------------------
+# counter-based uniform generator (identical on CPU and GPU: integer ops only
+# until the final scale, which is one exactly-rounded fp32 multiply)
+# ----------------------------------------------------------------------------
+_C1, _C2, _C3 = 0x1E3779B1, 0x05EBCA77, 0x42B2AE3D  # odd, < 2**31
+_M1, _M2 = 0x7FEB352D, 0x046CA68B                   # odd, < 2**31
+_MASK = 0xFFFFFFFF
+
+
+def _hash_u32(idx: torch.Tensor, seed: int, tensor_id: int) -> torch.Tensor:
+    """32-bit mix of (seed, tensor_id, flat index) in int64 arithmetic without overflow."""
+    x = (idx * _C1 + ((seed * _C2 + tensor_id * _C3) & _MASK)) & _MASK
+    x = x ^ (x >> 16)
+    x = (x * _M1) & _MASK
+    x = x ^ (x >> 15)
+    x = (x * _M2) & _MASK
+    x = x ^ (x >> 16)
+    return x
+
+
+def uniform_tensor(shape: Sequence[int], scale: float, seed: int, tensor_id: int,
+                   dtype: torch.dtype, device: str | torch.device = "cpu",
+                   chunk: int = 1 << 25) -> torch.Tensor:
+    """Values (2u-1)*scale with u = top 24 hash bits / 2**24, rounded to `dtype` (RNE)."""
+    n = int(np.prod(shape))
+    assert n < (1 << 31), "flat index must stay below 2**31"
+    out = torch.empty(n, dtype=dtype, device=device)
+    s = torch.tensor(scale, dtype=torch.float32, device=device)
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        idx = torch.arange(lo, hi, dtype=torch.int64, device=device)
+        h = _hash_u32(idx, seed, tensor_id)
+        u = (h >> 8).to(torch.float32) * (1.0 / (1 << 24))          # exact in fp32
+        out[lo:hi] = ((u * 2.0 - 1.0) * s).to(dtype)
+    return out.view(*shape)
+
+
+_TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def make_weights(shape: ModelShape, seed: int = 0, device: str | torch.device = "cpu") -> dict:
+    """Random-init Llama-style weights, all matrices stored [out, in] row-major.
+
+    Uniform(-s, s) with s = sqrt(3 / fan_in) (unit-variance-preserving), embedding
+    s = sqrt(3); norm gains are 1.  Returns
+    {"embed", "final_norm", "lm_head", "layers": [{"attn_norm","wq","wk","wv","wo",
+    "ffn_norm","w_gate","w_up","w_down"}, ...]} as torch tensors on `device`.
+    """
+    dt = _TORCH_DTYPE[shape.dtype]
+    d, hd = shape.d_model, shape.head_dim
+    hq, hk, f = shape.n_heads * hd, shape.n_kv_heads * hd, shape.d_ffn
+
+    def mat(out_f: int, in_f: int, tid: int) -> torch.Tensor:
+        return uniform_tensor((out_f, in_f), float(np.sqrt(3.0 / in_f)), seed, tid, dt, device)
+
+    w = {
+        "embed": uniform_tensor((shape.vocab, d), float(np.sqrt(3.0)), seed, 1, dt, device),
+        "final_norm": torch.ones(d, dtype=dt, device=device),
+        "lm_head": mat(shape.vocab, d, 2),
+        "layers": [],
+    }
+    for l in range(shape.n_layers):
+        base = 16 * (l + 1)
+        w["layers"].append({
+            "attn_norm": torch.ones(d, dtype=dt, device=device),
+            "wq": mat(hq, d, base + 0), "wk": mat(hk, d, base + 1), "wv": mat(hk, d, base + 2),
+            "wo": mat(d, hq, base + 3),
+            "ffn_norm": torch.ones(d, dtype=dt, device=device),
+            "w_gate": mat(f, d, base + 4), "w_up": mat(f, d, base + 5), "w_down": mat(d, f, base + 6),
+        })
+    return w
+
+
+def weights_to_numpy(w: dict) -> dict:
+    """Host float32 numpy copy of `make_weights` output (bf16 values are exact in fp32)."""
+    def cv(t: torch.Tensor) -> np.ndarray:
+        return t.detach().to("cpu").to(torch.float32).numpy()
+    return {
+        "embed": cv(w["embed"]), "final_norm": cv(w["final_norm"]), "lm_head": cv(w["lm_head"]),
+        "layers": [{k: cv(v) for k, v in layer.items()} for layer in w["layers"]],
+    }
+
+
+# ----------------------------------------------------------------------------
+# adjacency matrix, prompts, microbench tensors
+# ----------------------------------------------------------------------------
+def init_matrix(vocab: int, k: int) -> np.ndarray:
+    """M[i, j] = (i + j) mod V, int32 — the initial state the small config names."""
+    i = np.arange(vocab, dtype=np.int64)[:, None]
+    j = np.arange(k, dtype=np.int64)[None, :]
+    return ((i + j) % vocab).astype(np.int32)
+
+
+def zipf_prompt(vocab: int, length: int, seed: int, ngram: int = 4, n_plants: int | None = None,
+                alpha: float = 1.1) -> np.ndarray:
+    """Token ids with rank r drawn with p ~ r**-alpha (id = r - 1), plus planted repeats:
+    `n_plants` spans of `ngram` tokens copied from earlier in the prompt to later offsets."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    p = np.arange(1, vocab + 1, dtype=np.float64) ** (-alpha)
+    p /= p.sum()
+    toks = rng.choice(vocab, size=length, p=p).astype(np.int32)
+    if n_plants is None:
+        n_plants = max(1, length // (4 * ngram))
+    if length >= 3 * ngram:
+        for _ in range(n_plants):
+            src = int(rng.integers(0, length // 2 - ngram + 1))
+            dst = int(rng.integers(length // 2, length - ngram + 1))
+            toks[dst:dst + ngram] = toks[src:src + ngram]
+    return toks
+
+
+def normal_tensor(shape: Sequence[int], std: float, seed: int, dtype: torch.dtype,
+                  device: str | torch.device = "cpu") -> torch.Tensor:
+    """N(0, std) values generated on the host (seeded), rounded to `dtype`, moved to `device`."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    a = rng.standard_normal(size=tuple(shape), dtype=np.float32) * np.float32(std)
+    return torch.from_numpy(a).to(dtype).to(device)
+
+
+def random_tokens(vocab: int, n: int, seed: int) -> np.ndarray:
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return rng.integers(0, vocab, size=n).astype(np.int32)
+
+
+# ----------------------------------------------------------------------------
+# static tree templates (data only: parent index and candidate rank per node,
+# breadth-first / layer-major order, root first)
+# ----------------------------------------------------------------------------
+@dataclass(frozen=True)
+class TreeTemplate:
+    name: str
+    parent: np.ndarray  # int32 [N], parent[0] = -1
+    rank: np.ndarray    # int32 [N], rank[0] = -1; column of M[token(parent)]
+    n_layers: int
+    layer_sizes: Tuple[int, ...] = field(default=())
+
+    @property
+    def n_nodes(self) -> int:
+        return int(self.parent.shape[0])
+
+
+def template_from_child_counts(name: str, counts: List[List[int]]) -> TreeTemplate:
+    """counts[d][i] = number of children of the i-th node of layer d; child j takes rank j."""
+    parent, rank, sizes = [-1], [-1], [1]
+    layer_start, layer_size = 0, 1
+    for layer in counts:
+        assert len(layer) == layer_size, (name, len(layer), layer_size)
+        nxt = 0
+        for i, c in enumerate(layer):
+            for j in range(c):
+                parent.append(layer_start + i)
+                rank.append(j)
+                nxt += 1
+        layer_start += layer_size
+        layer_size = nxt
+        if nxt:
+            sizes.append(nxt)
+    return TreeTemplate(name, np.asarray(parent, np.int32), np.asarray(rank, np.int32),
+                        len(sizes), tuple(sizes))
+
+
+def _tree80_counts() -> List[List[int]]:
+    # 1 + 8 + 21 + 25 + 15 + 10 = 80 rows in 6 layers; earlier nodes of a layer get more
+    # children and go deeper (static + imbalanced, Section 3.2; the paper's own drawing
+    # is not available, its first two layer widths 8 and 21 are kept).
+    return [
+        [8],
+        [8, 4, 3, 2, 1, 1, 1, 1],
+        [5, 3, 2, 1, 1, 1, 1, 0, 2, 1, 1, 0, 2, 1, 0, 1, 0, 1, 1, 1, 0],
+        [4, 2, 1, 1, 0, 2, 1, 0, 1, 0, 1, 0, 0, 0, 1, 1, 0, 0, 0, 0, 0, 0, 0, 0, 0],
+        [3, 1, 1, 0, 1, 1, 1, 1, 1, 0, 0, 0, 0, 0, 0],
+    ]
+
+
+def tree80() -> TreeTemplate:
+    return template_from_child_counts("tree80", _tree80_counts())
+
+
+def tree81() -> TreeTemplate:
+    """The paper's row count (81 including the root, Appendix A.2): tree80 plus one leaf."""
+    c = _tree80_counts()
+    c[4][3] = 1
+    return template_from_child_counts("tree81", c)
+
+
+def tree15() -> TreeTemplate:
+    """15 rows, 4 layers: 1 + 4 + 8 + 2."""
+    return template_from_child_counts("tree15", [[4], [4, 2, 1, 1], [1, 1, 0, 0, 0, 0, 0, 0]])
+
+
+def tree15_alt() -> TreeTemplate:
+    """15 rows, 4 layers: 1 + 4 + 5 + 5."""
+    return template_from_child_counts("tree15_alt", [[4], [2, 1, 1, 1], [1, 1, 1, 1, 1]])
+
+
+def chain(n: int) -> TreeTemplate:
+    return template_from_child_counts(f"chain{n}", [[1]] * (n - 1)) if n > 1 else single()
+
+
+def single() -> TreeTemplate:
+    """Root only: the step degenerates to plain autoregressive decoding."""
+    return TreeTemplate("single", np.asarray([-1], np.int32), np.asarray([-1], np.int32), 1, (1,))
+
+
+def star(n_children: int) -> TreeTemplate:
+    return template_from_child_counts(f"star{n_children}", [[n_children]])
+
+
+def wide128() -> TreeTemplate:
+    """128 rows (the library maximum), 8 layers."""
+    c = _tree80_counts()
+    c[4] = [3, 2, 2, 1, 2, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1]          # 20
+    c.append([2, 2, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1])  # 22
+    c.append([1] * 16 + [0] * 6)                                   # 16
+    t = template_from_child_counts("wide128", c)
+    assert t.n_nodes == 128, t.n_nodes
+    return t
+
+
+TEMPLATES = {
+    "tree80": tree80, "tree81": tree81, "tree15": tree15, "tree15_alt": tree15_alt,
+    "single": single, "wide128": wide128,
+}
