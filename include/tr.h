@@ -1,0 +1,221 @@
+/*
+ * Token Recycling decode step for MI355X (gfx950) — C ABI.
+ *
+ * One decode step of the method is three calls on one HIP stream:
+ *
+ *   tr_build_tree         draft: gather the static draft tree from the adjacency matrix
+ *   tr_verify_forward     verify: one transformer forward over all tree nodes with tree
+ *                         attention, then the per-node top-k over the vocabulary
+ *   tr_accept_and_update  accept the longest correct root-to-node path, write every node's
+ *                         top-k into the adjacency matrix, compact the accepted K/V
+ *
+ * Conventions
+ *   - Every pointer is tagged [host] or [device] below.  Device pointers must belong to
+ *     the HIP device that was current at tr_create.
+ *   - Every function returns a tr_status and never throws.  All argument validation is done
+ *     on the host before the first HIP call of that function, so each error below can be
+ *     provoked without a GPU.
+ *   - After tr_create no function allocates device memory; scratch comes from the caller
+ *     through the workspace argument (size from tr_workspace_bytes).
+ *   - Work is enqueued on the given stream (a hipStream_t passed as void*; NULL = the
+ *     default stream).  Nothing synchronises unless stated.
+ *   - Calls on one tr_ctx must be issued from one thread at a time.
+ *   - Matrices are row-major.  Weight matrices are [out_features, in_features].
+ */
+#ifndef TR_H
+#define TR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TR_MAX_NODES 128  /* tree rows including the root                      */
+#define TR_MAX_LAYERS 32  /* tree layers including the root layer              */
+#define TR_MAX_K 32       /* candidates per token (columns of the matrix)      */
+
+typedef struct tr_ctx tr_ctx; /* opaque; owns the adjacency matrix and the device copy of the template */
+
+typedef enum {
+  TR_OK = 0,
+  TR_EINVAL = -1,    /* NULL pointer, non-positive size, inconsistent shapes, unsupported dtype */
+  TR_ETEMPLATE = -2, /* malformed tree template                                                */
+  TR_ENOMEM = -3,    /* host or device allocation failed (tr_create only)                      */
+  TR_EHIP = -4,      /* a HIP runtime call failed                                              */
+  TR_ECAPACITY = -5, /* KV cache or workspace too small for this call                          */
+  TR_ESTATE = -6     /* call made in a state that does not allow it                            */
+} tr_status;
+
+typedef enum { TR_F32 = 0, TR_BF16 = 1 } tr_dtype;
+
+/*
+ * Static draft tree (Section 3.2 "Draft Tree Retrieval", Appendix A.2): the shape is fixed
+ * across steps; node i is filled with the rank[i]-th candidate of its parent's token.
+ * Nodes are listed layer by layer (breadth-first), root first.  [host], copied at tr_create.
+ */
+typedef struct {
+  int32_t n_nodes;       /* N including the root, 1..TR_MAX_NODES                       */
+  int32_t n_layers;      /* D including the root layer, 1..TR_MAX_LAYERS                */
+  const int32_t *parent; /* [N]; parent[0] = -1; 0 <= parent[i] < i; depths non-decreasing */
+  const int32_t *rank;   /* [N]; rank[0] = -1; 0 <= rank[i] < k; (parent, rank) pairs unique */
+} tr_tree_template;
+
+/* Per-layer weights, [device], element type tr_model.dtype. */
+typedef struct {
+  const void *attn_norm; /* [d_model]                        */
+  const void *wq;        /* [n_heads * head_dim, d_model]    */
+  const void *wk;        /* [n_kv_heads * head_dim, d_model] */
+  const void *wv;        /* [n_kv_heads * head_dim, d_model] */
+  const void *wo;        /* [d_model, n_heads * head_dim]    */
+  const void *ffn_norm;  /* [d_model]                        */
+  const void *w_gate;    /* [d_ffn, d_model]                 */
+  const void *w_up;      /* [d_ffn, d_model]                 */
+  const void *w_down;    /* [d_model, d_ffn]                 */
+} tr_layer;
+
+/*
+ * Decoder-only transformer the draft tree is verified with (Section 2.2: one forward pass over
+ * the content plus all draft tokens).  The paper uses unmodified Llama-family checkpoints; this
+ * is that public architecture: pre-RMSNorm, rotary embedding with half-split pairing
+ * (i, i + head_dim/2), grouped-query attention scaled by 1/sqrt(head_dim), SwiGLU FFN, final
+ * RMSNorm, untied LM head, no biases.  The struct and the tr_layer array are [host]; the weight
+ * pointers inside are [device] and stay owned by the caller.
+ */
+typedef struct {
+  int32_t dtype; /* tr_dtype of every weight, of the embedding and of the KV cache */
+  int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_theta;
+  const void *embed;      /* [vocab, d_model] */
+  const tr_layer *layers; /* [host] array of n_layers entries */
+  const void *final_norm; /* [d_model] */
+  const void *lm_head;    /* [vocab, d_model] */
+} tr_model;
+
+/*
+ * KV cache, owned by the caller.  Positions 0..*d_len-1 are committed (the content so far);
+ * tr_verify_forward additionally writes the N tree nodes' keys/values at positions
+ * *d_len .. *d_len+N-1, and tr_accept_and_update moves the accepted ones to the front of that
+ * range.  Layout (element type dtype):
+ *   k: [n_layers][n_kv_heads][capacity][head_dim]
+ *   v: [n_layers][n_kv_heads][head_dim][capacity]      (position-contiguous, i.e. transposed)
+ * len_bound is a host-side upper bound of *d_len kept by the library so that capacity can be
+ * checked without reading the device: set both to the same value when (re)initialising.
+ */
+typedef struct {
+  int32_t dtype, n_layers, n_kv_heads, head_dim, capacity;
+  void *k;           /* [device] */
+  void *v;           /* [device] */
+  int32_t *d_len;    /* [device] one int32: committed length L */
+  int32_t len_bound; /* [host]   L <= len_bound always          */
+} tr_kv;
+
+/* Result of one step, written by tr_accept_and_update. */
+typedef struct {
+  int32_t n_accepted;             /* a: draft tokens confirmed, 0..D-1                          */
+  int32_t n_emitted;              /* a + 1: confirmed drafts plus the model's own next token    */
+  int32_t winner;                 /* tree node whose output is that next token                  */
+  int32_t next_root;              /* = emitted[a]; root of the next step's tree                 */
+  int32_t kv_len;                 /* committed length after the step                            */
+  int32_t path[TR_MAX_LAYERS];    /* node indices root..winner (a + 1 valid entries)            */
+  int32_t emitted[TR_MAX_LAYERS]; /* the a + 1 new tokens in order                              */
+} tr_step_out;
+
+/*
+ * Create a context for vocabulary size V and k candidates per token with a static tree.
+ * Allocates the adjacency matrix M[V, k] int32 on the current device, initialised to zero
+ * (Section 3.1), and the device copy of the template (depths, ancestor bitmasks, layer
+ * offsets).  Errors: TR_EINVAL (NULL, V <= 0, k <= 0 or > TR_MAX_K), TR_ETEMPLATE, TR_ENOMEM,
+ * TR_EHIP.  *out is set only on TR_OK and is released with tr_destroy.
+ */
+tr_status tr_create(int32_t V, int32_t k, const tr_tree_template *tree, tr_ctx **out);
+tr_status tr_destroy(tr_ctx *ctx);
+
+/*
+ * Copy the whole matrix from / to [host] memory, int32 [V * k], synchronously (hot start,
+ * Section 3.1: the matrix persists across queries and may be saved and restored).
+ */
+tr_status tr_matrix_load(tr_ctx *ctx, const int32_t *h_M);
+tr_status tr_matrix_store(tr_ctx *ctx, int32_t *h_M);
+
+/*
+ * Draft-tree retrieval (Section 3.2, Algorithm 1): S[0] = *d_root and, layer by layer,
+ * S[i] = M[S[parent[i]], rank[i]].  d_root [device] one int32 in [0, V); d_S [device] int32 [N],
+ * the merged sequence in breadth-first order.  A root outside [0, V) is clamped into range by
+ * the kernel (no error is reported from device code).
+ */
+tr_status tr_build_tree(tr_ctx *ctx, const int32_t *d_root, int32_t *d_S, void *stream);
+
+/* Bytes of [device] workspace tr_verify_forward / tr_prefill need for this model (256-aligned). */
+tr_status tr_workspace_bytes(const tr_ctx *ctx, const tr_model *model, size_t *bytes);
+
+/*
+ * Verification forward (Section 2.2 "Guess and Verify" and "Tree Attention"): runs the N tokens
+ * d_S through the model in one pass.  Node i sits at position L + depth(i) and attends to the
+ * committed positions 0..L-1 and to its own ancestors and itself — nothing else, exactly.
+ * Writes the nodes' keys/values to cache positions L..L+N-1, the logits to d_logits if it is not
+ * NULL ([device] float32 [N, vocab]), and the per-node candidates argtopk (Section 2.1) to
+ * d_topk ([device] int32 [N, k]): indices of the k largest logits, largest first, equal values
+ * ordered by increasing index (Appendix A.1 tie rule), -0 equal to +0.
+ * Errors: TR_EINVAL (NULL, model/cache/ctx shapes disagree, unsupported shape), TR_ECAPACITY
+ * (kv->len_bound + N > capacity, or workspace too small), TR_EHIP.
+ */
+tr_status tr_verify_forward(tr_ctx *ctx, const tr_model *model, tr_kv *kv, const int32_t *d_S,
+                            float *d_logits, int32_t *d_topk, void *d_workspace,
+                            size_t workspace_bytes, void *stream);
+
+/*
+ * Accept and update (Section 3.3 "Verification and Update").  With out[i] = d_topk[i, 0]:
+ * node i is correct when every draft token on its root-to-node path equals the output at that
+ * token's parent; the deepest correct node wins (smallest index among equals).  Then
+ *   - emitted = the winner's path tokens after the root, then out[winner];
+ *   - M[S[i], :] = d_topk[i, :] for ALL N nodes (accepted, rejected and the root); a token that
+ *     occurs several times keeps the candidates of its last occurrence (Appendix A.5 "Last",
+ *     one of the outcomes the paper's unordered update can produce);
+ *   - the path nodes' keys/values move to cache positions L..L+a and *kv->d_len becomes L+a+1.
+ * d_out [device] receives the result.  If h_out is not NULL ([host]) the result is also copied
+ * there and the stream is synchronised; kv->len_bound then becomes exact, otherwise it grows
+ * by the tree depth.  Errors: TR_EINVAL, TR_ECAPACITY, TR_EHIP.
+ */
+tr_status tr_accept_and_update(tr_ctx *ctx, tr_kv *kv, const int32_t *d_S, const int32_t *d_topk,
+                               tr_step_out *d_out, tr_step_out *h_out, void *stream);
+
+/*
+ * Prompt ingestion through the same kernels: runs d_tokens [device] int32 [n_tokens] causally
+ * after the committed prefix (a chain is a tree whose node i has ancestors 0..i), commits their
+ * keys/values and advances *kv->d_len and kv->len_bound by n_tokens.  No logits, no matrix
+ * update (the paper updates M only from decoding steps, Section 3.3).
+ */
+tr_status tr_prefill(tr_ctx *ctx, const tr_model *model, tr_kv *kv, const int32_t *d_tokens,
+                     int32_t n_tokens, void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Single operations of the step, exposed for kernel-level parity tests and microbenchmarks.
+ *
+ * tr_op_topk: argtopk of each of n_rows rows of d_logits ([device], dtype f32 or bf16,
+ *   [n_rows, V] with V the context's vocabulary) into d_topk [device] int32 [n_rows, k].
+ * tr_op_matrix_update: the M scatter of tr_accept_and_update alone, all N nodes, last wins.
+ * tr_op_tree_attention: the attention of one layer.  d_q [device] [N, n_heads, head_dim]
+ *   (already rotated), cache layer `layer` of kv holding L committed positions plus the N tree
+ *   nodes' keys/values at L..L+N-1; d_out [device] [N, n_heads, head_dim]; element type kv->dtype.
+ * tr_op_linear: y[n_rows, out_f] (float32) = x[n_rows, in_f] * w[out_f, in_f]^T, x and w of
+ *   element type dtype, through the same kernel the projections use.
+ */
+tr_status tr_op_topk(tr_ctx *ctx, const void *d_logits, int32_t dtype, int32_t n_rows,
+                     int32_t *d_topk, void *stream);
+tr_status tr_op_matrix_update(tr_ctx *ctx, const int32_t *d_S, const int32_t *d_topk, void *stream);
+tr_status tr_op_tree_attention(tr_ctx *ctx, const tr_kv *kv, int32_t layer, int32_t n_heads,
+                               const void *d_q, void *d_out, void *d_workspace,
+                               size_t workspace_bytes, void *stream);
+tr_status tr_op_linear(tr_ctx *ctx, const void *d_x, const void *d_w, int32_t dtype,
+                       int32_t n_rows, int32_t in_f, int32_t out_f, float *d_y,
+                       void *d_workspace, size_t workspace_bytes, void *stream);
+
+/* Static, never NULL. */
+const char *tr_strerror(tr_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TR_H */

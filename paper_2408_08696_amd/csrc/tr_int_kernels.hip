@@ -1,0 +1,267 @@
+// Integer kernels of the Token Recycling step: draft-tree gather, per-row top-k, greedy accept,
+// adjacency-matrix scatter and KV compaction.  All single-workgroup or tiny: the work is a few
+// KB of dependent L2 accesses, so each kernel is shaped to be one launch with no host round trip.
+#include "tr_internal.h"
+
+namespace tr {
+
+// ---------------------------------------------------------------------------------------------
+// Draft-tree retrieval (Section 3.2, Algorithm 1).  One workgroup; the tree lives in LDS and the
+// D-1 dependent gather rounds are separated by workgroup barriers.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(TR_MAX_NODES) void k_build_tree(const int32_t *__restrict__ M, int32_t V,
+                                                             int32_t k, TreeDev t,
+                                                             const int32_t *__restrict__ d_root,
+                                                             int32_t *__restrict__ S) {
+  __shared__ int32_t s[TR_MAX_NODES];
+  const int i = threadIdx.x;
+  const bool live = i < t.n_nodes;
+  const int par = live ? t.parent[i] : -1;
+  const int rk = live ? t.rank[i] : 0;
+  const int dep = live ? t.depth[i] : -1;
+  if (i == 0) {
+    int r = *d_root;
+    s[0] = r < 0 ? 0 : (r >= V ? V - 1 : r);
+  }
+  for (int d = 1; d < t.n_layers; ++d) {
+    __syncthreads();
+    if (dep == d) s[i] = M[(size_t)s[par] * k + rk];
+  }
+  __syncthreads();
+  if (live) S[i] = s[i];
+}
+
+hipError_t launch_build_tree(const tr_ctx *c, const int32_t *d_root, int32_t *d_S, hipStream_t st) {
+  hipLaunchKernelGGL(k_build_tree, dim3(1), dim3(TR_MAX_NODES), 0, st, c->d_M, c->V, c->k, c->tree,
+                     d_root, d_S);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// argtopk (Section 2.1): one workgroup per row, k selection passes.  Pass p finds the first
+// element, in the total order (value descending, index ascending), that comes strictly after the
+// winner of pass p-1.  Exact for ties and for -0 == +0; no per-thread candidate lists.
+// ---------------------------------------------------------------------------------------------
+struct Cand {
+  float v;
+  int32_t i;
+};
+__device__ inline bool before(const Cand &a, const Cand &b) { // a strictly precedes b
+  return a.v > b.v || (a.v == b.v && a.i < b.i);
+}
+
+constexpr int TOPK_THREADS = 512;
+
+template <typename T>
+__global__ __launch_bounds__(TOPK_THREADS) void k_topk(const T *__restrict__ logits, int32_t V, int32_t k,
+                                                        int32_t *__restrict__ out) {
+  __shared__ Cand red[TOPK_THREADS / 64];
+  __shared__ Cand winner;
+  const T *row = logits + (size_t)blockIdx.x * V;
+  const int tid = threadIdx.x;
+  Cand prev;
+  prev.v = __builtin_inff();
+  prev.i = -1; // precedes every real element
+  for (int p = 0; p < k; ++p) {
+    Cand best;
+    best.v = -__builtin_inff();
+    best.i = 0x7FFFFFFF; // follows every real element
+    for (int j = tid; j < V; j += TOPK_THREADS) {
+      Cand e;
+      e.v = to_f32<T>(row[j]);
+      e.i = j;
+      if (before(prev, e) && before(e, best)) best = e;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+      Cand o;
+      o.v = __shfl_xor(best.v, off);
+      o.i = __shfl_xor(best.i, off);
+      if (before(o, best)) best = o;
+    }
+    if ((tid & 63) == 0) red[tid >> 6] = best;
+    __syncthreads();
+    if (tid == 0) {
+      Cand b = red[0];
+      for (int w = 1; w < TOPK_THREADS / 64; ++w)
+        if (before(red[w], b)) b = red[w];
+      winner = b;
+      out[(size_t)blockIdx.x * k + p] = b.i;
+    }
+    __syncthreads();
+    prev = winner;
+  }
+}
+
+hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k,
+                       int32_t *d_topk, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  if (dtype == TR_BF16)
+    hipLaunchKernelGGL(k_topk<bf16_t>, dim3(rows), dim3(TOPK_THREADS), 0, st, (const bf16_t *)logits, V, k, d_topk);
+  else
+    hipLaunchKernelGGL(k_topk<float>, dim3(rows), dim3(TOPK_THREADS), 0, st, (const float *)logits, V, k, d_topk);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Matrix update (Section 3.3): M[S[i], :] = topk[i, :] for every node.  A token that occurs more
+// than once is written by its last occurrence only (Appendix A.5 "Last"), which makes the result
+// independent of thread scheduling.
+// ---------------------------------------------------------------------------------------------
+__device__ inline void scatter_rows(int32_t *__restrict__ M, int32_t k, int n_nodes, const int32_t *sS,
+                                    const int32_t *__restrict__ topk, int i) {
+  if (i >= n_nodes) return;
+  const int tok = sS[i];
+  for (int j = i + 1; j < n_nodes; ++j)
+    if (sS[j] == tok) return; // a later occurrence owns the row
+  for (int c = 0; c < k; ++c) M[(size_t)tok * k + c] = topk[(size_t)i * k + c];
+}
+
+__global__ __launch_bounds__(TR_MAX_NODES) void k_matrix_update(int32_t *__restrict__ M, int32_t V, int32_t k,
+                                                                int32_t n_nodes, const int32_t *__restrict__ S,
+                                                                const int32_t *__restrict__ topk) {
+  __shared__ int32_t sS[TR_MAX_NODES];
+  const int i = threadIdx.x;
+  if (i < n_nodes) {
+    int t = S[i];
+    sS[i] = t < 0 ? 0 : (t >= V ? V - 1 : t);
+  }
+  __syncthreads();
+  scatter_rows(M, k, n_nodes, sS, topk, i);
+}
+
+hipError_t launch_matrix_update(const tr_ctx *c, const int32_t *d_S, const int32_t *d_topk, hipStream_t st) {
+  hipLaunchKernelGGL(k_matrix_update, dim3(1), dim3(TR_MAX_NODES), 0, st, c->d_M, c->V, c->k,
+                     c->tree.n_nodes, d_S, d_topk);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Greedy accept + matrix update in one workgroup (Section 3.3 with the chain rule of Section 2.2).
+// match bit i  = draft token i equals the model output at its parent (root: always)
+// node i is ok = every bit of its ancestor mask is a match bit
+// winner       = deepest ok node, smallest index among equals
+// The kernel also publishes the committed length before the step (step_L) and advances *d_len, so
+// the compaction kernel that follows works from step_L and needs no further bookkeeping launch.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(TR_MAX_NODES) void k_accept_update(int32_t *__restrict__ M, int32_t V, int32_t k,
+                                                                TreeDev t, const int32_t *__restrict__ S,
+                                                                const int32_t *__restrict__ topk,
+                                                                int32_t *__restrict__ d_len,
+                                                                int32_t *__restrict__ step_L,
+                                                                tr_step_out *__restrict__ out) {
+  __shared__ int32_t sS[TR_MAX_NODES];
+  __shared__ int32_t sOut[TR_MAX_NODES];
+  __shared__ uint64_t mbits[2];
+  __shared__ int32_t best_key;
+  const int i = threadIdx.x;
+  const bool live = i < t.n_nodes;
+  if (i == 0) best_key = -1;
+  if (live) {
+    int tk = S[i];
+    sS[i] = tk < 0 ? 0 : (tk >= V ? V - 1 : tk);
+    sOut[i] = topk[(size_t)i * k];
+  }
+  __syncthreads();
+  const bool match = live && (i == 0 || sS[i] == sOut[t.parent[i]]);
+  const uint64_t ballot = __ballot(match);
+  if ((i & 63) == 0) mbits[i >> 6] = ballot;
+  __syncthreads();
+  if (live) {
+    const uint64_t a0 = t.anc[2 * i], a1 = t.anc[2 * i + 1];
+    const bool ok = ((mbits[0] & a0) == a0) && ((mbits[1] & a1) == a1);
+    if (ok) atomicMax(&best_key, t.depth[i] * 256 + (255 - i));
+  }
+  __syncthreads();
+  if (i == 0) {
+    const int w = 255 - (best_key & 255);
+    const int a = best_key >> 8;
+    uint64_t a0 = t.anc[2 * w], a1 = t.anc[2 * w + 1];
+    int cnt = 0;
+    // ancestors in increasing index order are the path root..winner (breadth-first numbering)
+    for (int j = 0; j < t.n_nodes; ++j) {
+      const bool on = j < 64 ? ((a0 >> j) & 1) : ((a1 >> (j - 64)) & 1);
+      if (on) {
+        out->path[cnt] = j;
+        if (cnt > 0) out->emitted[cnt - 1] = sS[j];
+        ++cnt;
+      }
+    }
+    const int bonus = sOut[w];
+    out->emitted[a] = bonus;
+    for (int j = cnt; j < TR_MAX_LAYERS; ++j) {
+      out->path[j] = -1;
+      out->emitted[j] = -1;
+    }
+    out->n_accepted = a;
+    out->n_emitted = a + 1;
+    out->winner = w;
+    out->next_root = bonus;
+    const int L = *d_len;
+    *step_L = L;
+    *d_len = L + a + 1;
+    out->kv_len = L + a + 1;
+  }
+  scatter_rows(M, k, t.n_nodes, sS, topk, i);
+}
+
+// ---------------------------------------------------------------------------------------------
+// KV compaction: the accepted path's keys/values (written by the forward at L + node index) move
+// to L + 0..a.  One workgroup per (layer, kv head); all sources are staged in LDS before any
+// destination is written, so overlapping source/destination positions are safe.
+//   K: [layers][Hkv][cap][hd]   V: [layers][Hkv][hd][cap]
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_compact_kv(T *__restrict__ K, T *__restrict__ Vt, int32_t cap, int32_t hd,
+                                                    const int32_t *__restrict__ step_L,
+                                                    const tr_step_out *__restrict__ out) {
+  extern __shared__ unsigned char smem_raw[];
+  T *sk = reinterpret_cast<T *>(smem_raw);          // [a+1][hd]
+  const int a = out->n_accepted;
+  if (a == 0) return;                                 // root already sits at L
+  T *sv = sk + (size_t)TR_MAX_LAYERS * hd;           // [a+1][hd]
+  const int L = *step_L;
+  const size_t blk = blockIdx.x;                     // layer * Hkv + head
+  T *Kb = K + blk * (size_t)cap * hd;
+  T *Vb = Vt + blk * (size_t)hd * cap;
+  const int total = (a + 1) * hd;
+  for (int e = threadIdx.x; e < total; e += blockDim.x) {
+    const int i = e / hd, d = e - i * hd;
+    const int src = L + out->path[i];
+    sk[e] = Kb[(size_t)src * hd + d];
+    sv[e] = Vb[(size_t)d * cap + src];
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < total; e += blockDim.x) {
+    const int i = e / hd, d = e - i * hd;
+    const int dst = L + i;
+    Kb[(size_t)dst * hd + d] = sk[e];
+    Vb[(size_t)d * cap + dst] = sv[e];
+  }
+}
+
+hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t *d_S, const int32_t *d_topk,
+                                tr_step_out *d_out, hipStream_t st) {
+  hipLaunchKernelGGL(k_accept_update, dim3(1), dim3(TR_MAX_NODES), 0, st, c->d_M, c->V, c->k, c->tree, d_S,
+                     d_topk, kv->d_len, c->d_step_L, d_out);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int blocks = kv->n_layers * kv->n_kv_heads;
+  const size_t esz = dtype_size(kv->dtype);
+  const size_t smem = 2 * (size_t)TR_MAX_LAYERS * kv->head_dim * esz;
+  if (kv->dtype == TR_BF16)
+    hipLaunchKernelGGL(k_compact_kv<bf16_t>, dim3(blocks), dim3(256), smem, st, (bf16_t *)kv->k, (bf16_t *)kv->v,
+                       kv->capacity, kv->head_dim, c->d_step_L, d_out);
+  else
+    hipLaunchKernelGGL(k_compact_kv<float>, dim3(blocks), dim3(256), smem, st, (float *)kv->k, (float *)kv->v,
+                       kv->capacity, kv->head_dim, c->d_step_L, d_out);
+  return hipGetLastError();
+}
+
+__global__ void k_advance_len(int32_t *d_len, int32_t by) { *d_len += by; }
+
+hipError_t launch_advance_len(int32_t *d_len, int32_t by, hipStream_t st) {
+  hipLaunchKernelGGL(k_advance_len, dim3(1), dim3(1), 0, st, d_len, by);
+  return hipGetLastError();
+}
+
+} // namespace tr

@@ -1,0 +1,113 @@
+// Internal declarations shared by the translation units of libtr (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "tr.h"
+
+namespace tr {
+
+// ---------------------------------------------------------------------------------------------
+// bf16 storage helpers (round-to-nearest-even; NaN inputs are not supported anywhere on the path)
+// ---------------------------------------------------------------------------------------------
+typedef uint16_t bf16_t;
+
+__host__ __device__ inline float bf16_to_f32(bf16_t b) {
+  union { uint32_t u; float f; } c;
+  c.u = ((uint32_t)b) << 16;
+  return c.f;
+}
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+  union { uint32_t u; float f; } c;
+  c.f = f;
+  uint32_t u = c.u;
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ inline float to_f32(T v);
+template <> __device__ inline float to_f32<float>(float v) { return v; }
+template <> __device__ inline float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ inline T from_f32(float v);
+template <> __device__ inline float from_f32<float>(float v) { return v; }
+template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+inline size_t dtype_size(int32_t dt) { return dt == TR_BF16 ? 2 : 4; }
+
+// ---------------------------------------------------------------------------------------------
+// device copy of a tree: node i sits depth[i] below the root and may attend to the tree nodes
+// whose bits are set in anc[i] (its ancestors and itself; 128 bits as two 64-bit words)
+// ---------------------------------------------------------------------------------------------
+struct TreeDev {
+  int32_t n_nodes;
+  int32_t n_layers;
+  const int32_t *parent; // [n]
+  const int32_t *rank;   // [n]
+  const int32_t *depth;  // [n]
+  const uint64_t *anc;   // [n][2]
+};
+
+// Shapes of one forward pass, passed by value to launch helpers.
+struct FwdDims {
+  int32_t n;      // rows (tree nodes or prefill chunk)
+  int32_t d, H, Hkv, hd, F, V;
+  int32_t cap;    // KV capacity (positions)
+  float eps, theta;
+};
+
+// Workspace carve-up (byte offsets, all 256-aligned).  Buffers are sized for TR_MAX_NODES rows.
+struct Workspace {
+  size_t x;        // float  [NP, d]            residual stream
+  size_t xn;       // T      [NP, d]            normalised activations
+  size_t qkv;      // float  [NP, (H+2Hkv)*hd]
+  size_t q;        // T      [NP, H*hd]         rotated queries
+  size_t attn;     // T      [NP, H*hd]         attention output
+  size_t gu;       // float  [NP, 2F]           gate | up (generic path only)
+  size_t h;        // T      [NP, F]            silu(gate)*up
+  size_t rope;     // float  [NP, hd]           cos[hd/2] | sin[hd/2] per row
+  size_t logits;   // float  [NP, V]            used when the caller passes no logits buffer
+  size_t part_ml;  // float  [SPLITS, NP, H, 2] attention split partials: running max, sum
+  size_t part_acc; // float  [SPLITS, NP, H, hd]
+  size_t total;
+};
+constexpr int NP = TR_MAX_NODES;
+constexpr int ATTN_MAX_SPLITS = 16;
+
+Workspace plan_workspace(const tr_model &m);
+
+} // namespace tr
+
+struct tr_ctx {
+  int32_t V, k;
+  int32_t device;
+  int32_t *d_M;          // [V, k]
+  tr::TreeDev tree;      // the static draft tree
+  tr::TreeDev chain;     // chain of TR_MAX_NODES nodes (prefill chunks)
+  void *d_tree_blob;     // backing store of both trees
+  int32_t *d_step_L;     // committed length at the start of the current accept/update
+  int32_t h_depth[TR_MAX_NODES];
+};
+
+namespace tr {
+
+// --- integer kernels (tr_int_kernels.hip) -------------------------------------------------------
+hipError_t launch_build_tree(const tr_ctx *c, const int32_t *d_root, int32_t *d_S, hipStream_t s);
+hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k,
+                       int32_t *d_topk, hipStream_t s);
+hipError_t launch_matrix_update(const tr_ctx *c, const int32_t *d_S, const int32_t *d_topk, hipStream_t s);
+hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t *d_S,
+                                const int32_t *d_topk, tr_step_out *d_out, hipStream_t s);
+hipError_t launch_advance_len(int32_t *d_len, int32_t by, hipStream_t s);
+
+// --- forward pass (tr_forward.hip) -----------------------------------------------------------------
+// Runs rows `tokens` through the model.  `write_logits` may be NULL (no LM head).
+hipError_t run_forward(const tr_model &m, const tr_kv &kv, const TreeDev &tree, int32_t n,
+                       const int32_t *d_tokens, float *write_logits, void *ws, hipStream_t s);
+hipError_t run_tree_attention(const tr_kv &kv, int32_t layer, int32_t H, const TreeDev &tree,
+                              const void *d_q, void *d_out, void *ws, hipStream_t s);
+hipError_t run_linear(const void *x, const void *w, int32_t dtype, int32_t n, int32_t in_f,
+                      int32_t out_f, float *y, hipStream_t s);
+
+} // namespace tr

@@ -1,0 +1,81 @@
+"""Helpers shared by the GPU parity tests (no method arithmetic here)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import tr_oracle as O
+from paper_2408_08696_amd import synth, tr
+
+
+def require_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    if not os.path.exists(tr.LIB_PATH):
+        pytest.fail("libtr.so is missing on a GPU box: build it before running GPU tests")
+    tr.lib()
+
+
+def to_gpu(w):
+    return {k: (v.cuda() if not isinstance(v, list) else [{a: b.cuda() for a, b in l.items()} for l in v])
+            for k, v in w.items()}
+
+
+def oracle_cfg(sh):
+    return O.Config(sh.n_layers, sh.d_model, sh.n_heads, sh.n_kv_heads, sh.head_dim, sh.d_ffn, sh.vocab,
+                    sh.rms_eps, sh.rope_theta)
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def lockstep(eng, sh, w_np, tmpl, prompt, n_steps, M0, k=8, rel_tol=2e-2, abs_tol=None, dtype=np.float64,
+             label=""):
+    """Teacher-forced parity of whole steps.  Each step the oracle starts from the same integer
+    state as the GPU (root, M, committed tokens), its logits are compared under the tolerance, and
+    its integer pipeline (top-k, accept, matrix update) is applied to the GPU's own logits and must
+    reproduce the GPU's integers bit for bit.  Returns per-step stats."""
+    cfg = oracle_cfg(sh)
+    tree = O.make_tree(tmpl.parent, tmpl.rank, k)
+    eng.ctx.matrix_load(M0)
+    eng.prefill(prompt)
+    M = M0.astype(np.int64).copy()
+    kv = O.KVCache(cfg, len(prompt) + n_steps * tree.n_layers + tree.n_nodes + 8, dtype)
+    O.prefill(cfg, w_np, kv, list(prompt[:-1]), dtype)
+    root = int(prompt[-1])
+    stats = []
+    for step in range(n_steps):
+        say(f"lockstep {label} step {step} L={kv.len}")
+        h = eng.step(sync=True)
+        S = O.build_tree(M, tree, root)
+        assert eng.S.cpu().tolist() == S.tolist(), f"step {step}: tree differs"
+        pos = [kv.len + int(d) for d in tree.depth]
+        lo, nk, nv = O.forward_nodes(cfg, w_np, kv, S, pos, tree.paths, dtype)
+        lg = eng.logits.cpu().numpy().astype(np.float64)
+        err = np.abs(lg - lo).max(axis=1)
+        scale = np.abs(lo).max(axis=1)
+        if abs_tol is not None:
+            assert err.max() <= abs_tol, f"step {step}: logits differ by {err.max()}"
+        else:
+            assert (err <= rel_tol * scale).all(), f"step {step}: rel err {np.max(err / scale)}"
+        topk, acc = O.integer_pipeline(M, tree, S, lg, k)          # oracle integers on the GPU's logits
+        assert np.array_equal(eng.topk.cpu().numpy().astype(np.int64), topk), f"step {step}: top-k differs"
+        assert h.n_accepted == acc.n_accepted and h.winner == acc.winner
+        assert list(h.path[:h.n_emitted]) == acc.path and list(h.emitted[:h.n_emitted]) == acc.emitted
+        assert h.next_root == acc.bonus and h.kv_len == kv.len + acc.n_accepted + 1
+        assert np.array_equal(eng.ctx.matrix_store().astype(np.int64), M), f"step {step}: matrix differs"
+        # rows whose own-logit top-k differs from the GPU's must be near-ties within the error
+        flips = 0
+        for n in range(tree.n_nodes):
+            mine = O.topk_ids(lo[n], k)
+            if not np.array_equal(mine, topk[n]):
+                flips += 1
+                srt = -np.sort(-lo[n])[:k + 1]
+                assert np.min(srt[:-1] - srt[1:]) <= 2 * err[n] + 1e-12, f"step {step} row {n}: flip without near-tie"
+        O.commit(kv, nk, nv, acc.path)
+        root = acc.bonus
+        stats.append(dict(step=step, max_err=float(err.max()), max_rel=float(np.max(err / scale)), flips=flips,
+                          n_emitted=acc.n_accepted + 1))
+    return stats, kv

@@ -1,0 +1,131 @@
+"""GPU parity of the verification forward and of whole decode steps against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tr_oracle as O
+from paper_2408_08696_amd import synth, tr
+from gpu_util import lockstep, oracle_cfg, require_gpu, say, to_gpu
+from test_oracle_loop import FIXTURE_MIN_GAP, fixture_min_gap
+
+pytestmark = pytest.mark.gpu
+K = 8
+
+
+@pytest.mark.parametrize("tmpl_name", ["tree15", "tree15_alt", "single"])
+def test_tiny_fp32_free_running(tmpl_name):
+    """The small fp32 config end to end, free running: 64 new tokens; emitted tokens, trees,
+    accepted lengths and M bit-exact, logits within 1e-4 absolute — and within a quarter of the
+    smallest top-k gap of the run, so no decision could have flipped."""
+    require_gpu()
+    sh = synth.SHAPES["tiny"]
+    tmpl = synth.TEMPLATES[tmpl_name]()
+    w = synth.make_weights(sh, seed=0)
+    wn = synth.weights_to_numpy(w)
+    prompt = synth.zipf_prompt(sh.vocab, 64, seed=0, ngram=4).tolist()
+    M0 = synth.init_matrix(sh.vocab, K)
+    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=64 + 64 + tmpl.n_nodes + 8)
+    eng.ctx.matrix_load(M0)
+    eng.prefill(prompt)
+
+    cfg = oracle_cfg(sh)
+    tree = O.make_tree(tmpl.parent, tmpl.rank, K)
+    M = M0.astype(np.int64)
+    steps = []
+    toks, lens, kv = O.tr_generate(cfg, wn, M, tree, prompt, 64, K, on_step=steps.append)
+    M_run = M0.astype(np.int64)
+    got, max_err = [], 0.0
+    for i, r in enumerate(steps):
+        say("tiny fp32", tmpl_name, "step", i)
+        h = eng.step(sync=True)
+        assert eng.S.cpu().tolist() == r.S.tolist(), f"step {i}: tree"
+        max_err = max(max_err, float(np.abs(eng.logits.cpu().numpy() - r.logits).max()))
+        assert np.array_equal(eng.topk.cpu().numpy(), r.topk), f"step {i}: top-k"
+        assert h.n_accepted == r.acc.n_accepted and list(h.path[:h.n_emitted]) == r.acc.path
+        assert list(h.emitted[:h.n_emitted]) == r.acc.emitted
+        got.extend(h.emitted[:h.n_emitted])
+        O.update_matrix(M_run, r.S, r.topk)
+        assert np.array_equal(eng.ctx.matrix_store().astype(np.int64), M_run), f"step {i}: matrix"
+    assert got[:64] == toks
+    ar, _, _ = O.ar_generate(cfg, wn, prompt, 64)
+    assert got[:64] == ar                                     # lossless on the GPU too
+    say("max |logit error|", max_err)
+    assert max_err < 1e-4
+    if tmpl_name == "tree15":
+        assert 4 * max_err < FIXTURE_MIN_GAP <= fixture_min_gap(0)
+    # committed KV equals the oracle's cache (K as stored, V transposed)
+    L = kv.len
+    kg = eng.kv.k[:, :, :L, :].permute(0, 2, 1, 3).cpu().numpy()
+    vg = eng.kv.v[:, :, :, :L].permute(0, 3, 1, 2).cpu().numpy()
+    for l in range(sh.n_layers):
+        assert np.abs(kg[l] - kv.k[l][:L]).max() < 1e-4 and np.abs(vg[l] - kv.v[l][:L]).max() < 1e-4
+
+
+@pytest.mark.parametrize("shape_name,tmpl_name", [("tiny_bf16", "tree80"), ("tiny_gqa_bf16", "tree80"),
+                                                  ("tiny_bf16", "tree81"), ("tiny_bf16", "wide128"),
+                                                  ("tiny_bf16", "single"), ("tiny", "tree80")])
+def test_small_shapes_lockstep(shape_name, tmpl_name):
+    require_gpu()
+    sh = synth.SHAPES[shape_name]
+    tmpl = synth.TEMPLATES[tmpl_name]()
+    w = synth.make_weights(sh, seed=1)
+    prompt = synth.zipf_prompt(sh.vocab, 150, seed=3, ngram=8).tolist()
+    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=512)
+    abs_tol = 1e-4 if sh.dtype == "f32" else None
+    stats, _ = lockstep(eng, sh, synth.weights_to_numpy(w), tmpl, prompt, 6, synth.init_matrix(sh.vocab, K),
+                        abs_tol=abs_tol, label=f"{shape_name}/{tmpl_name}")
+    say(stats)
+
+
+def test_prefill_crosses_chunk_boundaries():
+    """A 300-token prompt goes through three chain chunks (128 + 128 + 43); the cache must equal
+    the oracle's causal prefill."""
+    require_gpu()
+    sh = synth.SHAPES["tiny"]
+    w = synth.make_weights(sh, seed=2)
+    wn = synth.weights_to_numpy(w)
+    prompt = synth.zipf_prompt(sh.vocab, 300, seed=1).tolist()
+    eng = tr.Engine(sh, to_gpu(w), synth.tree15(), k=K, capacity=400)
+    eng.prefill(prompt)
+    torch.cuda.synchronize()
+    assert int(eng.kv.d_len.item()) == 299 and eng.kv.c.len_bound == 299
+    cfg = oracle_cfg(sh)
+    kv = O.KVCache(cfg, 400)
+    O.prefill(cfg, wn, kv, prompt[:-1])
+    kg = eng.kv.k[:, :, :299, :].permute(0, 2, 1, 3).cpu().numpy()
+    vg = eng.kv.v[:, :, :, :299].permute(0, 3, 1, 2).cpu().numpy()
+    for l in range(sh.n_layers):
+        assert np.abs(kg[l] - kv.k[l][:299]).max() < 1e-4
+        assert np.abs(vg[l] - kv.v[l][:299]).max() < 1e-4
+
+
+def test_capacity_is_checked_on_the_host():
+    require_gpu()
+    sh = synth.SHAPES["tiny"]
+    w = synth.make_weights(sh, seed=2)
+    tmpl = synth.tree15()
+    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=40)
+    with pytest.raises(tr.TRError) as e:
+        eng.prefill(list(range(60)))
+    assert e.value.status == tr.TR_ECAPACITY
+    eng.prefill(list(range(30)))
+    with pytest.raises(tr.TRError) as e:
+        eng.step()                                            # 29 + 15 > 40
+    assert e.value.status == tr.TR_ECAPACITY
+
+
+@pytest.mark.parametrize("n,K_,O_", [(80, 4096, 4096), (80, 11008, 4096), (81, 4096, 1024), (1, 4096, 512),
+                                     (128, 512, 2048), (16, 256, 64), (80, 1024, 32000)])
+def test_linear_bf16_matches_oracle_matmul(n, K_, O_):
+    """The projection kernel alone against a float64 matrix product of the same bf16 values."""
+    require_gpu()
+    say("linear", n, K_, O_)
+    x = synth.normal_tensor((n, K_), 1.0, seed=n + K_, dtype=torch.bfloat16)
+    w = synth.uniform_tensor((O_, K_), float(np.sqrt(3.0 / K_)), seed=5, tensor_id=O_, dtype=torch.bfloat16)
+    ctx = tr.Context(16, 8, [-1], [-1], 1)
+    y = torch.zeros(n, O_, dtype=torch.float32, device="cuda")
+    ctx.op_linear(x.cuda(), w.cuda(), y)
+    ref = x.double().numpy() @ w.double().numpy().T
+    err = np.abs(y.cpu().numpy() - ref).max()
+    say("max err", err)
+    assert err < 2e-5 * np.sqrt(K_)                           # fp32 accumulation of K products of O(1/sqrt(K))
