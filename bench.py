@@ -1,0 +1,181 @@
+"""Benchmark of the Token Recycling decode step on one MI355X.
+
+A "step" is one pass of the whole hot path: draft-tree gather, verification forward over the
+80 tree nodes (tree attention, all projections, LM head), per-node top-k, greedy accept, matrix
+update and KV compaction.  Workload: random-init 7B-shape Llama in bf16, batch 1, 80-node /
+6-layer static tree, k = 8, seeded Zipf(1.1) prompt of 512 tokens with planted 8-gram repeats;
+all inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line (see the keys below).  `--gpus N` with N > 1 is refused: this build is
+single-GPU by design.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--shape", default="7b")
+    ap.add_argument("--prompt-len", type=int, default=512)
+    ap.add_argument("--profile-steps", type=int, default=4)
+    ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--no-ar", action="store_true", help="skip the 1-node autoregressive comparison run")
+    ap.add_argument("--no-hot", action="store_true", help="skip the hot-start rerun")
+    return ap.parse_args()
+
+
+def timed_steps(eng, torch, n):
+    torch.cuda.synchronize()
+    l0 = int(eng.kv.d_len.item())
+    t0 = time.perf_counter()
+    for _ in range(n):
+        eng.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return dt, int(eng.kv.d_len.item()) - l0
+
+
+def cpu_baseline(sh, w_gpu, tmpl, prompt, n_steps, synth):
+    """The oracle as it stands, float32 batched mode, on the host cores: n_steps whole steps at the
+    same shape after a KV prefix of synthetic N(0,1) values (the oracle's own prefill of 511 tokens
+    would take minutes and is not part of a step)."""
+    import numpy as np
+    from oracle import tr_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    wn = synth.weights_to_numpy(w_gpu)
+    cfg = O.Config(sh.n_layers, sh.d_model, sh.n_heads, sh.n_kv_heads, sh.head_dim, sh.d_ffn, sh.vocab,
+                   sh.rms_eps, sh.rope_theta)
+    tree = O.make_tree(tmpl.parent, tmpl.rank, 8)
+    L = len(prompt) - 1
+    kv = O.KVCache(cfg, L + n_steps * tree.n_layers + tree.n_nodes, np.float32)
+    rng = np.random.default_rng(0)
+    for l in range(cfg.n_layers):
+        kv.k[l][:L] = rng.standard_normal((L, cfg.n_kv_heads, cfg.head_dim), dtype=np.float32)
+        kv.v[l][:L] = rng.standard_normal((L, cfg.n_kv_heads, cfg.head_dim), dtype=np.float32)
+    kv.len = L
+    M = synth.init_matrix(sh.vocab, 8).astype(np.int64)
+    root, emitted = int(prompt[-1]), 0
+    t0 = time.perf_counter()
+    for _ in range(n_steps):
+        r = O.tr_step(cfg, wn, kv, M, tree, root, 8, dtype=np.float32)
+        root = r.acc.bonus
+        emitted += r.acc.n_accepted + 1
+    dt = time.perf_counter() - t0
+    return {"value": n_steps / dt, "unit": "steps/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_steps} whole draft-verify-update steps, {sh.name} shape, float32 batched mode, "
+                      f"KV prefix of {L} synthetic N(0,1) positions", "s_per_step": dt / n_steps,
+            "tokens_per_s": emitted / dt}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              f"--gpus {a.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2408_08696_amd import synth, tr
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    tr.lib()
+    torch.cuda.set_device(0)
+    sh = synth.SHAPES[a.shape]
+    tmpl = synth.tree80()
+    K = 8
+    w = synth.make_weights(sh, seed=0, device="cuda")
+    prompt = synth.zipf_prompt(sh.vocab, a.prompt_len, seed=0, ngram=8).tolist()
+    M0 = synth.init_matrix(sh.vocab, K)
+    total_steps = a.warmup + a.steps + a.profile_steps
+    cap = a.prompt_len + total_steps * tmpl.n_layers + tmpl.n_nodes + 64
+
+    eng = tr.Engine(sh, w, tmpl, k=K, capacity=cap, keep_logits=False)
+    eng.ctx.matrix_load(M0)
+    eng.prefill(prompt)
+    timed_steps(eng, torch, a.warmup)
+    dt, toks = timed_steps(eng, torch, a.steps)
+    ms_step = dt / a.steps * 1e3
+    steps_s = a.steps / dt
+    mat = toks / a.steps
+
+    # per-kernel-class durations from HIP events on the same stream, same launch configuration
+    eng.ctx.profile_enable(True)
+    timed_steps(eng, torch, a.profile_steps)
+    prof = eng.ctx.profile_read()
+    eng.ctx.profile_enable(False)
+    breakdown = {k: {"launches_per_step": v[0] / a.profile_steps, "ms_per_step": v[1] / a.profile_steps}
+                 for k, v in prof.items()}
+    gu_launches, gu_ms = prof["gate_up_swiglu"]
+    gu_bytes = 2 * sh.d_ffn * sh.d_model * 2                       # gate + up weights, bf16, read once
+    gu_avg_s = gu_ms / gu_launches * 1e-3
+    achieved = gu_bytes / gu_avg_s / 1e9
+    roofline = {"kernel": "gate_up_swiglu (k_gemm_mfma, fused gate/up projection + SwiGLU)", "bound": "hbm",
+                "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
+                "traffic": None, "avg_launch_us": gu_avg_s * 1e6, "algorithmic_bytes_per_launch": gu_bytes}
+    wbytes = sh.weight_params() * 2
+    step_roofline = {"weight_bytes": wbytes, "ms_at_peak_hbm": wbytes / (PEAK_HBM_GBS * 1e9) * 1e3,
+                     "frac": wbytes / (PEAK_HBM_GBS * 1e9) * 1e3 / ms_step}
+
+    out = {
+        "metric": "TR steps/s, 7B-shape bf16, 1 GPU", "value": steps_s, "unit": "steps/s", "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{sh.name}-shape random-init Llama bf16, batch 1, {tmpl.n_nodes}-node "
+                               f"{tmpl.n_layers}-layer static tree, k=8, Zipf(1.1) prompt of {a.prompt_len} tokens "
+                               "with planted 8-gram repeats, M init (i+j) mod V",
+                   "n_layers": sh.n_layers, "d_model": sh.d_model, "vocab": sh.vocab},
+        "tokens_per_s": steps_s * mat, "mat": mat, "step_roofline": step_roofline, "roofline": roofline,
+        "breakdown_ms_per_step": breakdown,
+    }
+
+    if not a.no_hot:
+        # hot start (Section 3.1): same prompt again with the matrix the run above left behind
+        eng.prefill(prompt)
+        _, toks_hot = timed_steps(eng, torch, a.steps)
+        out["mat_hot_start"] = toks_hot / a.steps
+        out["tokens_per_s_hot_start"] = steps_s * toks_hot / a.steps
+    del eng
+
+    if not a.no_ar:
+        ar = tr.Engine(sh, w, synth.single(), k=K, capacity=a.prompt_len + a.warmup + a.steps + 64, keep_logits=False)
+        ar.ctx.matrix_load(M0)
+        ar.prefill(prompt)
+        timed_steps(ar, torch, a.warmup)
+        dt_ar, toks_ar = timed_steps(ar, torch, a.steps)
+        out["ar_tokens_per_s"] = toks_ar / dt_ar
+        out["ar_ms_per_step"] = dt_ar / a.steps * 1e3
+        out["speedup_vs_ar"] = out["tokens_per_s"] / out["ar_tokens_per_s"]
+        out["step_cost_ratio_vs_ar"] = ms_step / out["ar_ms_per_step"]
+        if "tokens_per_s_hot_start" in out:
+            out["speedup_vs_ar_hot_start"] = out["tokens_per_s_hot_start"] / out["ar_tokens_per_s"]
+        del ar
+
+    if a.cpu_steps > 0:
+        out["cpu_baseline"] = cpu_baseline(sh, w, tmpl, prompt, a.cpu_steps, synth)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

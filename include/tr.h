@@ -51,6 +51,19 @@ typedef enum {
 typedef enum { TR_F32 = 0, TR_BF16 = 1 } tr_dtype;
 
 /*
+ * Storage order of the projection and LM-head matrices of a model.
+ *   TR_ROW_MAJOR : [out_features, in_features] row-major.
+ *   TR_PACKED    : bf16 only; the order the MI355X matrix cores consume directly (written by
+ *                  tr_pack_weight): the matrix is cut into tiles of 16 out-features x 32
+ *                  in-features, tile (o/16, i/32) stored at ((o/16) * (in/32) + i/32) KiB, and inside
+ *                  a tile element (o, i) sits at 16-byte slot (o%16) + 16*((i%32)/8), element i%8.
+ *                  Needs out_features % 32 == 0 and in_features % 32 == 0.  This is the fast path;
+ *                  row-major models run through slower shape-generic kernels.
+ * The embedding table and the norm gains are always plain arrays.
+ */
+typedef enum { TR_ROW_MAJOR = 0, TR_PACKED = 1 } tr_layout;
+
+/*
  * Static draft tree (Section 3.2 "Draft Tree Retrieval", Appendix A.2): the shape is fixed
  * across steps; node i is filled with the rank[i]-th candidate of its parent's token.
  * Nodes are listed layer by layer (breadth-first), root first.  [host], copied at tr_create.
@@ -84,7 +97,8 @@ typedef struct {
  * pointers inside are [device] and stay owned by the caller.
  */
 typedef struct {
-  int32_t dtype; /* tr_dtype of every weight, of the embedding and of the KV cache */
+  int32_t dtype;  /* tr_dtype of every weight, of the embedding and of the KV cache */
+  int32_t layout; /* tr_layout of wq..w_down and lm_head                             */
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   float rms_eps, rope_theta;
   const void *embed;      /* [vocab, d_model] */
@@ -147,6 +161,12 @@ tr_status tr_matrix_store(tr_ctx *ctx, int32_t *h_M);
  */
 tr_status tr_build_tree(tr_ctx *ctx, const int32_t *d_root, int32_t *d_S, void *stream);
 
+/*
+ * Repack one row-major bf16 matrix d_src [out_f, in_f] into TR_PACKED order at d_dst (same size,
+ * must not overlap), on the stream.  Errors: TR_EINVAL (NULL, sizes not multiples of 32).
+ */
+tr_status tr_pack_weight(const void *d_src, void *d_dst, int32_t out_f, int32_t in_f, void *stream);
+
 /* Bytes of [device] workspace tr_verify_forward / tr_prefill need for this model (256-aligned). */
 tr_status tr_workspace_bytes(const tr_ctx *ctx, const tr_model *model, size_t *bytes);
 
@@ -199,8 +219,10 @@ tr_status tr_prefill(tr_ctx *ctx, const tr_model *model, tr_kv *kv, const int32_
  * tr_op_tree_attention: the attention of one layer.  d_q [device] [N, n_heads, head_dim]
  *   (already rotated), cache layer `layer` of kv holding L committed positions plus the N tree
  *   nodes' keys/values at L..L+N-1; d_out [device] [N, n_heads, head_dim]; element type kv->dtype.
- * tr_op_linear: y[n_rows, out_f] (float32) = x[n_rows, in_f] * w[out_f, in_f]^T, x and w of
- *   element type dtype, through the same kernel the projections use.
+ * tr_op_linear: y[n_rows, out_f] (float32) = x[n_rows, in_f] * w[out_f, in_f]^T, x row-major and w
+ *   row-major or packed (layout), both of element type dtype.  With TR_PACKED the call goes through
+ *   the kernel the projections use (x is rearranged into the workspace first; `splits` partial sums
+ *   over in_f are added up in order); with TR_ROW_MAJOR through the generic kernel (splits ignored).
  */
 tr_status tr_op_topk(tr_ctx *ctx, const void *d_logits, int32_t dtype, int32_t n_rows,
                      int32_t *d_topk, void *stream);
@@ -208,9 +230,26 @@ tr_status tr_op_matrix_update(tr_ctx *ctx, const int32_t *d_S, const int32_t *d_
 tr_status tr_op_tree_attention(tr_ctx *ctx, const tr_kv *kv, int32_t layer, int32_t n_heads,
                                const void *d_q, void *d_out, void *d_workspace,
                                size_t workspace_bytes, void *stream);
-tr_status tr_op_linear(tr_ctx *ctx, const void *d_x, const void *d_w, int32_t dtype,
-                       int32_t n_rows, int32_t in_f, int32_t out_f, float *d_y,
+tr_status tr_op_linear(tr_ctx *ctx, const void *d_x, const void *d_w, int32_t dtype, int32_t layout,
+                       int32_t n_rows, int32_t in_f, int32_t out_f, int32_t splits, float *d_y,
                        void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Per-kernel timing for the time-allocation breakdown (the paper's Figure 6 reports the same
+ * split: retrieval / model forward / verification / update).  While enabled, every kernel the
+ * step calls launch is bracketed by HIP events on the caller's stream; tr_profile_read
+ * synchronises the device, sums elapsed times per kernel class, returns up to max_entries
+ * entries ([host]) and resets the counters.  Enabling allocates the event pool (the only
+ * allocation after tr_create); events beyond the pool are silently not recorded.
+ */
+typedef struct {
+  char name[24];
+  int32_t launches;
+  double ms;            /* total elapsed over those launches */
+} tr_profile_entry;
+tr_status tr_profile_enable(tr_ctx *ctx, int32_t enable);
+tr_status tr_profile_read(tr_ctx *ctx, tr_profile_entry *h_entries, int32_t max_entries,
+                          int32_t *n_entries);
 
 /* Static, never NULL. */
 const char *tr_strerror(tr_status status);

@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include "tr_internal.h"
+#include "tr_kernels.h"
 
 using namespace tr;
 
@@ -44,6 +45,8 @@ tr_status check_model(const tr_model *m) {
   if (m->head_dim % 2 != 0 || m->head_dim > 256) return TR_EINVAL;
   if (m->d_model % 4 != 0 || m->d_ffn % 4 != 0) return TR_EINVAL;
   if (!(m->rms_eps >= 0.f) || !(m->rope_theta > 0.f)) return TR_EINVAL;
+  if (m->layout != TR_ROW_MAJOR && m->layout != TR_PACKED) return TR_EINVAL;
+  if (!model_layout_ok(*m)) return TR_EINVAL;
   if (m->embed == nullptr || m->layers == nullptr || m->final_norm == nullptr || m->lm_head == nullptr)
     return TR_EINVAL;
   for (int l = 0; l < m->n_layers; ++l) {
@@ -158,6 +161,11 @@ tr_status tr_create(int32_t V, int32_t k, const tr_tree_template *t, tr_ctx **ou
 
 tr_status tr_destroy(tr_ctx *c) {
   if (c == nullptr) return TR_EINVAL;
+  if (c->prof.ev != nullptr) {
+    for (int i = 0; i < 2 * Profiler::MAX_PAIRS; ++i) (void)hipEventDestroy(c->prof.ev[i]);
+    delete[] c->prof.ev;
+    delete[] c->prof.cat;
+  }
   hipError_t e1 = hipFree(c->d_M), e2 = hipFree(c->d_tree_blob);
   delete c;
   return (e1 == hipSuccess && e2 == hipSuccess) ? TR_OK : TR_EHIP;
@@ -180,6 +188,7 @@ tr_status tr_matrix_store(tr_ctx *c, int32_t *h_M) {
 
 tr_status tr_build_tree(tr_ctx *c, const int32_t *d_root, int32_t *d_S, void *stream) {
   if (c == nullptr || d_root == nullptr || d_S == nullptr) return TR_EINVAL;
+  ProfScope ps(&c->prof, PC_BUILD, as_stream(stream));
   return launch_build_tree(c, d_root, d_S, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;
 }
 
@@ -202,7 +211,8 @@ tr_status tr_verify_forward(tr_ctx *c, const tr_model *m, tr_kv *kv, const int32
   if (ws_bytes < w.total) return TR_ECAPACITY;
   float *logits = d_logits != nullptr ? d_logits : reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + w.logits);
   hipStream_t st = as_stream(stream);
-  if (run_forward(*m, *kv, c->tree, n, d_S, logits, ws, st) != hipSuccess) return TR_EHIP;
+  if (run_forward(*m, *kv, c->tree, n, d_S, logits, ws, &c->prof, st) != hipSuccess) return TR_EHIP;
+  ProfScope ps(&c->prof, PC_TOPK, st);
   if (launch_topk(logits, TR_F32, n, m->vocab, c->k, d_topk, st) != hipSuccess) return TR_EHIP;
   return TR_OK;
 }
@@ -214,7 +224,10 @@ tr_status tr_accept_and_update(tr_ctx *c, tr_kv *kv, const int32_t *d_S, const i
   if (s != TR_OK) return s;
   if ((int64_t)kv->len_bound + c->tree.n_nodes > kv->capacity) return TR_ECAPACITY;
   hipStream_t st = as_stream(stream);
-  if (launch_accept_update(c, kv, d_S, d_topk, d_out, st) != hipSuccess) return TR_EHIP;
+  {
+    ProfScope ps(&c->prof, PC_ACCEPT, st);
+    if (launch_accept_update(c, kv, d_S, d_topk, d_out, st) != hipSuccess) return TR_EHIP;
+  }
   if (h_out != nullptr) {
     if (hipMemcpyAsync(h_out, d_out, sizeof(tr_step_out), hipMemcpyDeviceToHost, st) != hipSuccess) return TR_EHIP;
     if (hipStreamSynchronize(st) != hipSuccess) return TR_EHIP;
@@ -235,7 +248,7 @@ tr_status tr_prefill(tr_ctx *c, const tr_model *m, tr_kv *kv, const int32_t *d_t
   hipStream_t st = as_stream(stream);
   for (int lo = 0; lo < n_tokens; lo += TR_MAX_NODES) {
     const int n = n_tokens - lo < TR_MAX_NODES ? n_tokens - lo : TR_MAX_NODES;
-    if (run_forward(*m, *kv, c->chain, n, d_tokens + lo, nullptr, ws, st) != hipSuccess) return TR_EHIP;
+    if (run_forward(*m, *kv, c->chain, n, d_tokens + lo, nullptr, ws, nullptr, st) != hipSuccess) return TR_EHIP;
     if (launch_advance_len(kv->d_len, n, st) != hipSuccess) return TR_EHIP;
     kv->len_bound += n;
   }
@@ -267,14 +280,72 @@ tr_status tr_op_tree_attention(tr_ctx *c, const tr_kv *kv, int32_t layer, int32_
                                                                                                             : TR_EHIP;
 }
 
-tr_status tr_op_linear(tr_ctx *c, const void *d_x, const void *d_w, int32_t dtype, int32_t n_rows, int32_t in_f,
-                       int32_t out_f, float *d_y, void *ws, size_t ws_bytes, void *stream) {
-  (void)ws;
-  (void)ws_bytes;
+tr_status tr_op_linear(tr_ctx *c, const void *d_x, const void *d_w, int32_t dtype, int32_t layout, int32_t n_rows,
+                       int32_t in_f, int32_t out_f, int32_t splits, float *d_y, void *ws, size_t ws_bytes,
+                       void *stream) {
   if (c == nullptr || d_x == nullptr || d_w == nullptr || d_y == nullptr) return TR_EINVAL;
   if (dtype != TR_F32 && dtype != TR_BF16) return TR_EINVAL;
+  if (layout != TR_ROW_MAJOR && layout != TR_PACKED) return TR_EINVAL;
   if (n_rows <= 0 || n_rows > TR_MAX_NODES || in_f <= 0 || out_f <= 0) return TR_EINVAL;
-  return run_linear(d_x, d_w, dtype, n_rows, in_f, out_f, d_y, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;
+  if (layout == TR_PACKED) {
+    if (dtype != TR_BF16 || !gemm_mfma_supported(n_rows, in_f, out_f)) return TR_EINVAL;
+    if (splits < 1 || splits > GEMM_MAX_SPLITS) return TR_EINVAL;
+    if (ws == nullptr || ws_bytes < linear_workspace_bytes(n_rows, in_f, out_f, splits)) return TR_ECAPACITY;
+  }
+  return run_linear(d_x, d_w, dtype, layout, n_rows, in_f, out_f, splits, d_y, ws, as_stream(stream)) == hipSuccess
+             ? TR_OK
+             : TR_EHIP;
+}
+
+tr_status tr_pack_weight(const void *d_src, void *d_dst, int32_t out_f, int32_t in_f, void *stream) {
+  if (d_src == nullptr || d_dst == nullptr || d_src == d_dst) return TR_EINVAL;
+  if (out_f <= 0 || in_f <= 0 || out_f % 32 != 0 || in_f % 32 != 0) return TR_EINVAL;
+  return launch_pack_weight((const bf16_t *)d_src, (bf16_t *)d_dst, out_f, in_f, as_stream(stream)) == hipSuccess
+             ? TR_OK
+             : TR_EHIP;
+}
+
+tr_status tr_profile_enable(tr_ctx *c, int32_t enable) {
+  if (c == nullptr) return TR_EINVAL;
+  Profiler &p = c->prof;
+  if (enable && p.ev == nullptr) {
+    p.ev = new (std::nothrow) hipEvent_t[2 * Profiler::MAX_PAIRS];
+    p.cat = new (std::nothrow) int8_t[Profiler::MAX_PAIRS];
+    if (p.ev == nullptr || p.cat == nullptr) return TR_ENOMEM;
+    for (int i = 0; i < 2 * Profiler::MAX_PAIRS; ++i)
+      if (hipEventCreate(&p.ev[i]) != hipSuccess) return TR_EHIP;
+  }
+  p.enabled = enable != 0;
+  return TR_OK;
+}
+
+tr_status tr_profile_read(tr_ctx *c, tr_profile_entry *h, int32_t max_entries, int32_t *n_entries) {
+  static const char *const names[PC_COUNT] = {"build_tree", "embed_rope_table", "rmsnorm", "qkv_proj", "rope_kv_write",
+                                              "tree_attention", "o_proj", "gate_up_swiglu", "down_proj", "lm_head",
+                                              "topk", "accept_update_compact"};
+  if (c == nullptr || h == nullptr || n_entries == nullptr || max_entries < 0) return TR_EINVAL;
+  Profiler &p = c->prof;
+  if (hipDeviceSynchronize() != hipSuccess) return TR_EHIP;
+  double ms[PC_COUNT] = {0};
+  int cnt[PC_COUNT] = {0};
+  for (int i = 0; i < p.used; ++i) {
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, p.ev[2 * i], p.ev[2 * i + 1]) != hipSuccess) return TR_EHIP;
+    ms[p.cat[i]] += t;
+    cnt[p.cat[i]] += 1;
+  }
+  p.used = 0;
+  int n = 0;
+  for (int k = 0; k < PC_COUNT && n < max_entries; ++k) {
+    if (cnt[k] == 0) continue;
+    memset(&h[n], 0, sizeof(h[n]));
+    strncpy(h[n].name, names[k], sizeof(h[n].name) - 1);
+    h[n].launches = cnt[k];
+    h[n].ms = ms[k];
+    ++n;
+  }
+  *n_entries = n;
+  return TR_OK;
 }
 
 } // extern "C"

@@ -7,7 +7,7 @@ namespace tr {
 bool attn_mfma_supported(int32_t, int32_t) { return false; }
 
 hipError_t launch_attn_mfma(const bf16_t *, const bf16_t *, const bf16_t *, int32_t, int32_t, int32_t, int32_t,
-                            const uint64_t *, const int32_t *, int32_t, float *, float *, bf16_t *, hipStream_t) {
+                            const uint64_t *, const int32_t *, int32_t, float *, float *, bf16_t *, int32_t, hipStream_t) {
   return hipErrorNotSupported;
 }
 

@@ -30,6 +30,7 @@ Workspace plan_workspace(const tr_model &m) {
   w.logits = take((size_t)NP * m.vocab * 4);
   w.part_ml = take((size_t)ATTN_MAX_SPLITS * NP * m.n_heads * 2 * 4);
   w.part_acc = take((size_t)ATTN_MAX_SPLITS * NP * m.n_heads * m.head_dim * 4);
+  w.ypart = take((size_t)GEMM_MAX_SPLITS * NP * m.d_model * 4);
   w.total = off;
   return w;
 }
@@ -184,7 +185,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_attn_generic(const T *__restrict__ q, const T *__restrict__ Kl,
                                                       const T *__restrict__ Vl, int32_t H, int32_t Hkv, int32_t hd,
                                                       int32_t cap, int32_t n_nodes, const uint64_t *__restrict__ anc,
-                                                      const int32_t *__restrict__ d_len, T *__restrict__ out) {
+                                                      const int32_t *__restrict__ d_len, T *__restrict__ out,
+                                                      int32_t out_row_tiles) {
   __shared__ float sq[256];
   __shared__ float sp[256];
   __shared__ float red[4];
@@ -240,7 +242,12 @@ __global__ __launch_bounds__(256) void k_attn_generic(const T *__restrict__ q, c
     }
     __syncthreads();
   }
-  if (tid < hd) out[((size_t)n * H + h) * hd + tid] = from_f32<T>(acc / l);
+  if (tid < hd) {
+    // row-major [n, H*hd], or fragment order for the o-projection when out_row_tiles > 0
+    const size_t idx = out_row_tiles > 0 ? act_frag_index(n, h * hd + tid, out_row_tiles)
+                                         : ((size_t)n * H + h) * hd + tid;
+    out[idx] = from_f32<T>(acc / l);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -254,32 +261,28 @@ __global__ __launch_bounds__(256) void k_attn_generic(const T *__restrict__ q, c
 
 template <typename T>
 static hipError_t attention_dispatch(const tr_kv &kv, int32_t layer, int32_t H, const TreeDev &tree, int32_t n,
-                                     const T *q, T *out, const Workspace *w, unsigned char *ws, hipStream_t st) {
+                                     const T *q, T *out, int32_t out_row_tiles, float *part_ml, float *part_acc,
+                                     hipStream_t st) {
   const size_t lsz = (size_t)kv.n_kv_heads * kv.capacity * kv.head_dim;
   const T *Kl = (const T *)kv.k + (size_t)layer * lsz;
   const T *Vl = (const T *)kv.v + (size_t)layer * lsz;
-  if (sizeof(T) == 2 && attn_mfma_supported(kv.head_dim, n) && w != nullptr) {
+  if (sizeof(T) == 2 && attn_mfma_supported(kv.head_dim, n) && part_ml != nullptr) {
     return launch_attn_mfma((const bf16_t *)q, (const bf16_t *)Kl, (const bf16_t *)Vl, H, kv.n_kv_heads, kv.capacity,
-                            n, tree.anc, kv.d_len, kv.len_bound + n, (float *)(ws + w->part_ml),
-                            (float *)(ws + w->part_acc), (bf16_t *)out, st);
+                            n, tree.anc, kv.d_len, kv.len_bound + n, part_ml, part_acc, (bf16_t *)out, out_row_tiles,
+                            st);
   }
   hipLaunchKernelGGL(k_attn_generic<T>, dim3(n, H), dim3(256), 0, st, q, Kl, Vl, H, kv.n_kv_heads, kv.head_dim,
-                     kv.capacity, n, tree.anc, kv.d_len, out);
+                     kv.capacity, n, tree.anc, kv.d_len, out, out_row_tiles);
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// generic forward: row-major weights, any shape, f32 or bf16 storage
+// ---------------------------------------------------------------------------------------------
 template <typename T>
-static hipError_t linear_dispatch(const T *a, const T *w, int32_t n, int32_t K, int32_t O, float *y, int32_t ldy,
-                                  int32_t mode, hipStream_t st) {
-  if (sizeof(T) == 2 && gemm_mfma_supported(n, K, O))
-    return launch_gemm_mfma((const bf16_t *)a, (const bf16_t *)w, nullptr, n, K, O, y, ldy,
-                            mode ? GEMM_ADD : GEMM_STORE, nullptr, st);
-  return linear_generic<T>(a, w, n, K, O, y, ldy, mode, st);
-}
-
-template <typename T>
-static hipError_t forward_t(const tr_model &m, const tr_kv &kv, const TreeDev &tree, int32_t n, const int32_t *tok,
-                            float *logits_out, unsigned char *ws, hipStream_t st) {
+static hipError_t forward_generic(const tr_model &m, const tr_kv &kv, const TreeDev &tree, int32_t n,
+                                  const int32_t *tok, float *logits_out, unsigned char *ws, Profiler *prof,
+                                  hipStream_t st) {
   const Workspace w = plan_workspace(m);
   const int d = m.d_model, H = m.n_heads, Hkv = m.n_kv_heads, hd = m.head_dim, F = m.d_ffn;
   const int hq = H * hd, hk = Hkv * hd, wq = hq + 2 * hk;
@@ -293,65 +296,306 @@ static hipError_t forward_t(const tr_model &m, const tr_kv &kv, const TreeDev &t
   float *rope = (float *)(ws + w.rope);
   const size_t lsz = (size_t)Hkv * kv.capacity * hd;
 
-  hipLaunchKernelGGL(k_embed_rope<T>, dim3(n), dim3(256), 0, st, (const T *)m.embed, m.vocab, d, tok, tree.depth,
-                     kv.d_len, hd, m.rope_theta, x, rope);
-  TR_TRY(hipGetLastError());
+  {
+    ProfScope ps(prof, PC_EMBED, st);
+    hipLaunchKernelGGL(k_embed_rope<T>, dim3(n), dim3(256), 0, st, (const T *)m.embed, m.vocab, d, tok, tree.depth,
+                       kv.d_len, hd, m.rope_theta, x, rope);
+    TR_TRY(hipGetLastError());
+  }
   for (int l = 0; l < m.n_layers; ++l) {
     const tr_layer &lw = m.layers[l];
-    hipLaunchKernelGGL(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, x, (const T *)lw.attn_norm, d, m.rms_eps, xn);
-    TR_TRY(hipGetLastError());
-    TR_TRY(linear_dispatch<T>(xn, (const T *)lw.wq, n, d, hq, qkv, wq, 0, st));
-    TR_TRY(linear_dispatch<T>(xn, (const T *)lw.wk, n, d, hk, qkv + hq, wq, 0, st));
-    TR_TRY(linear_dispatch<T>(xn, (const T *)lw.wv, n, d, hk, qkv + hq + hk, wq, 0, st));
-    hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, rope, H, Hkv, hd, kv.capacity,
-                       kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz);
-    TR_TRY(hipGetLastError());
-    TR_TRY(attention_dispatch<T>(kv, l, H, tree, n, q, attn, &w, ws, st));
-    TR_TRY(linear_dispatch<T>(attn, (const T *)lw.wo, n, hq, d, x, d, 1, st));
-    hipLaunchKernelGGL(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, x, (const T *)lw.ffn_norm, d, m.rms_eps, xn);
-    TR_TRY(hipGetLastError());
-    if (sizeof(T) == 2 && gemm_mfma_supported(n, d, F)) {
-      TR_TRY(launch_gemm_mfma((const bf16_t *)xn, (const bf16_t *)lw.w_gate, (const bf16_t *)lw.w_up, n, d, F, nullptr,
-                              F, GEMM_SWIGLU, (bf16_t *)hbuf, st));
-    } else {
+    {
+      ProfScope ps(prof, PC_NORM, st);
+      hipLaunchKernelGGL(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, x, (const T *)lw.attn_norm, d, m.rms_eps, xn);
+      TR_TRY(hipGetLastError());
+    }
+    {
+      ProfScope ps(prof, PC_QKV, st);
+      TR_TRY(linear_generic<T>(xn, lw.wq, n, d, hq, qkv, wq, 0, st));
+      TR_TRY(linear_generic<T>(xn, lw.wk, n, d, hk, qkv + hq, wq, 0, st));
+      TR_TRY(linear_generic<T>(xn, lw.wv, n, d, hk, qkv + hq + hk, wq, 0, st));
+    }
+    {
+      ProfScope ps(prof, PC_ROPE, st);
+      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, rope, H, Hkv, hd, kv.capacity,
+                         kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz);
+      TR_TRY(hipGetLastError());
+    }
+    {
+      ProfScope ps(prof, PC_ATTN, st);
+      TR_TRY(attention_dispatch<T>(kv, l, H, tree, n, q, attn, 0, (float *)(ws + w.part_ml),
+                                   (float *)(ws + w.part_acc), st));
+    }
+    {
+      ProfScope ps(prof, PC_OPROJ, st);
+      TR_TRY(linear_generic<T>(attn, lw.wo, n, hq, d, x, d, 1, st));
+    }
+    {
+      ProfScope ps(prof, PC_NORM, st);
+      hipLaunchKernelGGL(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, x, (const T *)lw.ffn_norm, d, m.rms_eps, xn);
+      TR_TRY(hipGetLastError());
+    }
+    {
+      ProfScope ps(prof, PC_GATEUP, st);
       TR_TRY(linear_generic<T>(xn, lw.w_gate, n, d, F, gu, 2 * F, 0, st));
       TR_TRY(linear_generic<T>(xn, lw.w_up, n, d, F, gu + F, 2 * F, 0, st));
       hipLaunchKernelGGL(k_swiglu<T>, dim3((F + 255) / 256, n), dim3(256), 0, st, gu, F, hbuf);
       TR_TRY(hipGetLastError());
     }
-    TR_TRY(linear_dispatch<T>(hbuf, (const T *)lw.w_down, n, F, d, x, d, 1, st));
+    {
+      ProfScope ps(prof, PC_DOWN, st);
+      TR_TRY(linear_generic<T>(hbuf, lw.w_down, n, F, d, x, d, 1, st));
+    }
   }
   if (logits_out != nullptr) {
-    hipLaunchKernelGGL(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, x, (const T *)m.final_norm, d, m.rms_eps, xn);
+    {
+      ProfScope ps(prof, PC_NORM, st);
+      hipLaunchKernelGGL(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, x, (const T *)m.final_norm, d, m.rms_eps, xn);
+      TR_TRY(hipGetLastError());
+    }
+    ProfScope ps(prof, PC_LMHEAD, st);
+    TR_TRY(linear_generic<T>(xn, m.lm_head, n, d, m.vocab, logits_out, m.vocab, 0, st));
+  }
+  return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------------------------
+// packed bf16 forward: MFMA GEMMs on packed weights, activations handed from kernel to kernel in
+// fragment order, projection outputs that feed the residual stream kept as per-split partial sums
+// which the next normalisation kernel folds into x in a fixed order.
+// ---------------------------------------------------------------------------------------------
+// x[row,:] += sum_s part[s][row,:]  (n_part may be 0), then xn = bf16(rmsnorm(x) * g) in fragment order.
+// Rows n..16*row_tiles-1 are written as zeros.
+__global__ __launch_bounds__(256) void k_addnorm_frag(float *__restrict__ x, const float *__restrict__ part,
+                                                      int32_t n_part, size_t part_stride, const bf16_t *__restrict__ g,
+                                                      int32_t n, int32_t d, float eps, int32_t row_tiles,
+                                                      bf16_t *__restrict__ xn_frag) {
+  __shared__ float red[4];
+  const int row = blockIdx.x;
+  const bool live = row < n;
+  float *xr = x + (size_t)row * d;
+  float ss = 0.f;
+  if (live) {
+    for (int j = threadIdx.x * 4; j < d; j += 1024) {
+      float4 v = *reinterpret_cast<const float4 *>(xr + j);
+      for (int s = 0; s < n_part; ++s) {
+        const float4 p = *reinterpret_cast<const float4 *>(part + (size_t)s * part_stride + (size_t)row * d + j);
+        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+      }
+      if (n_part > 0) *reinterpret_cast<float4 *>(xr + j) = v;
+      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+  }
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float r = 1.0f / sqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)d + eps);
+  for (int j = threadIdx.x * 8; j < d; j += 2048) {
+    uint4 pk = uint4{0u, 0u, 0u, 0u};
+    if (live) {
+      const float4 a = *reinterpret_cast<const float4 *>(xr + j), b = *reinterpret_cast<const float4 *>(xr + j + 4);
+      const uint4 gv = *reinterpret_cast<const uint4 *>(g + j);
+      const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+      const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w};
+      uint32_t o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float g0 = bf16_to_f32((bf16_t)(gw[e] & 0xFFFFu)), g1 = bf16_to_f32((bf16_t)(gw[e] >> 16));
+        o[e] = (uint32_t)f32_to_bf16(v[2 * e] * r * g0) | ((uint32_t)f32_to_bf16(v[2 * e + 1] * r * g1) << 16);
+      }
+      pk = uint4{o[0], o[1], o[2], o[3]};
+    }
+    *reinterpret_cast<uint4 *>(xn_frag + act_frag_index(row, j, row_tiles)) = pk;
+  }
+}
+
+// row-major bf16 [n, K] -> fragment order (standalone linear op only)
+__global__ __launch_bounds__(256) void k_rows_to_frag(const bf16_t *__restrict__ a, int32_t n, int32_t K,
+                                                      int32_t row_tiles, bf16_t *__restrict__ frag) {
+  const int row = blockIdx.x;
+  for (int j = threadIdx.x * 8; j < K; j += 2048) {
+    uint4 v = uint4{0u, 0u, 0u, 0u};
+    if (row < n) v = *reinterpret_cast<const uint4 *>(a + (size_t)row * K + j);
+    *reinterpret_cast<uint4 *>(frag + act_frag_index(row, j, row_tiles)) = v;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_sum_parts(const float *__restrict__ part, int32_t n_part, size_t part_stride,
+                                                   size_t count, float *__restrict__ y) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  float v = part[i];
+  for (int s = 1; s < n_part; ++s) v += part[(size_t)s * part_stride + i];
+  y[i] = v;
+}
+
+static int choose_splits(int out_tiles) {
+  int s = 1;
+  while (s < GEMM_MAX_SPLITS && (out_tiles / 2) * s < 256) s *= 2;
+  return s;
+}
+
+static bool packed_supported(const tr_model &m) {
+  const int hq = m.n_heads * m.head_dim, hk = m.n_kv_heads * m.head_dim;
+  return m.dtype == TR_BF16 && m.layout == TR_PACKED && m.d_model % 32 == 0 && m.d_ffn % 32 == 0 && hq % 32 == 0 &&
+         hk % 32 == 0 && m.vocab % 32 == 0;
+}
+
+static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeDev &tree, int32_t n, const int32_t *tok,
+                                 float *logits_out, unsigned char *ws, Profiler *prof, hipStream_t st) {
+  typedef bf16_t T;
+  const Workspace w = plan_workspace(m);
+  const int d = m.d_model, H = m.n_heads, Hkv = m.n_kv_heads, hd = m.head_dim, F = m.d_ffn;
+  const int hq = H * hd, hk = Hkv * hd, wq = hq + 2 * hk;
+  const int NT = (n + 15) / 16;
+  float *x = (float *)(ws + w.x);
+  T *xn = (T *)(ws + w.xn);
+  float *qkv = (float *)(ws + w.qkv);
+  T *q = (T *)(ws + w.q);
+  T *attn = (T *)(ws + w.attn);
+  T *hbuf = (T *)(ws + w.h);
+  float *rope = (float *)(ws + w.rope);
+  float *ypart = (float *)(ws + w.ypart);
+  const size_t ystride = (size_t)NP * d;
+  const size_t lsz = (size_t)Hkv * kv.capacity * hd;
+  const int s_d = choose_splits(d / 16); // K-splits of the two projections that feed the residual stream
+
+  {
+    ProfScope ps(prof, PC_EMBED, st);
+    hipLaunchKernelGGL(k_embed_rope<T>, dim3(n), dim3(256), 0, st, (const T *)m.embed, m.vocab, d, tok, tree.depth,
+                       kv.d_len, hd, m.rope_theta, x, rope);
     TR_TRY(hipGetLastError());
-    TR_TRY(linear_dispatch<T>(xn, (const T *)m.lm_head, n, d, m.vocab, logits_out, m.vocab, 0, st));
+  }
+  int pending = 0; // partial sums waiting in ypart
+  for (int l = 0; l < m.n_layers; ++l) {
+    const tr_layer &lw = m.layers[l];
+    {
+      ProfScope ps(prof, PC_NORM, st);
+      hipLaunchKernelGGL(k_addnorm_frag, dim3(NT * 16), dim3(256), 0, st, x, ypart, pending, ystride,
+                         (const T *)lw.attn_norm, n, d, m.rms_eps, NT, xn);
+      TR_TRY(hipGetLastError());
+    }
+    {
+      ProfScope ps(prof, PC_QKV, st);
+      GemmArgs g{};
+      g.a_frag = xn; g.n = n; g.K = d;
+      g.seg[0] = GemmSeg{(const T *)lw.wq, hq / 16};
+      g.seg[1] = GemmSeg{(const T *)lw.wk, hk / 16};
+      g.seg[2] = GemmSeg{(const T *)lw.wv, hk / 16};
+      g.n_seg = 3; g.y = qkv; g.ldy = wq; g.splits = 1; g.split_stride = 0; g.mode = GEMM_STORE;
+      TR_TRY(launch_gemm_mfma(g, st));
+    }
+    {
+      ProfScope ps(prof, PC_ROPE, st);
+      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, rope, H, Hkv, hd, kv.capacity,
+                         kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz);
+      TR_TRY(hipGetLastError());
+    }
+    {
+      ProfScope ps(prof, PC_ATTN, st);
+      TR_TRY(attention_dispatch<T>(kv, l, H, tree, n, q, attn, NT, (float *)(ws + w.part_ml),
+                                   (float *)(ws + w.part_acc), st));
+    }
+    {
+      ProfScope ps(prof, PC_OPROJ, st);
+      GemmArgs g{};
+      g.a_frag = attn; g.n = n; g.K = hq;
+      g.seg[0] = GemmSeg{(const T *)lw.wo, d / 16};
+      g.n_seg = 1; g.y = ypart; g.ldy = d; g.splits = s_d; g.split_stride = ystride; g.mode = GEMM_STORE;
+      TR_TRY(launch_gemm_mfma(g, st));
+    }
+    {
+      ProfScope ps(prof, PC_NORM, st);
+      hipLaunchKernelGGL(k_addnorm_frag, dim3(NT * 16), dim3(256), 0, st, x, ypart, s_d, ystride,
+                         (const T *)lw.ffn_norm, n, d, m.rms_eps, NT, xn);
+      TR_TRY(hipGetLastError());
+    }
+    {
+      ProfScope ps(prof, PC_GATEUP, st);
+      GemmArgs g{};
+      g.a_frag = xn; g.n = n; g.K = d;
+      g.seg[0] = GemmSeg{(const T *)lw.w_gate, F / 16};
+      g.n_seg = 1; g.w2 = (const T *)lw.w_up; g.splits = 1; g.h_frag = hbuf; g.mode = GEMM_SWIGLU;
+      TR_TRY(launch_gemm_mfma(g, st));
+    }
+    {
+      ProfScope ps(prof, PC_DOWN, st);
+      GemmArgs g{};
+      g.a_frag = hbuf; g.n = n; g.K = F;
+      g.seg[0] = GemmSeg{(const T *)lw.w_down, d / 16};
+      g.n_seg = 1; g.y = ypart; g.ldy = d; g.splits = s_d; g.split_stride = ystride; g.mode = GEMM_STORE;
+      TR_TRY(launch_gemm_mfma(g, st));
+    }
+    pending = s_d;
+  }
+  if (logits_out != nullptr) {
+    {
+      ProfScope ps(prof, PC_NORM, st);
+      hipLaunchKernelGGL(k_addnorm_frag, dim3(NT * 16), dim3(256), 0, st, x, ypart, pending, ystride,
+                         (const T *)m.final_norm, n, d, m.rms_eps, NT, xn);
+      TR_TRY(hipGetLastError());
+    }
+    ProfScope ps(prof, PC_LMHEAD, st);
+    GemmArgs g{};
+    g.a_frag = xn; g.n = n; g.K = d;
+    g.seg[0] = GemmSeg{(const T *)m.lm_head, m.vocab / 16};
+    g.n_seg = 1; g.y = logits_out; g.ldy = m.vocab; g.splits = 1; g.split_stride = 0; g.mode = GEMM_STORE;
+    TR_TRY(launch_gemm_mfma(g, st));
   }
   return hipSuccess;
 }
 
 hipError_t run_forward(const tr_model &m, const tr_kv &kv, const TreeDev &tree, int32_t n, const int32_t *d_tokens,
-                       float *write_logits, void *ws, hipStream_t st) {
-  if (m.dtype == TR_BF16) return forward_t<bf16_t>(m, kv, tree, n, d_tokens, write_logits, (unsigned char *)ws, st);
-  return forward_t<float>(m, kv, tree, n, d_tokens, write_logits, (unsigned char *)ws, st);
+                       float *write_logits, void *ws, Profiler *prof, hipStream_t st) {
+  if (packed_supported(m)) return forward_packed(m, kv, tree, n, d_tokens, write_logits, (unsigned char *)ws, prof, st);
+  if (m.dtype == TR_BF16)
+    return forward_generic<bf16_t>(m, kv, tree, n, d_tokens, write_logits, (unsigned char *)ws, prof, st);
+  return forward_generic<float>(m, kv, tree, n, d_tokens, write_logits, (unsigned char *)ws, prof, st);
 }
+
+bool model_layout_ok(const tr_model &m) { return m.layout == TR_ROW_MAJOR || packed_supported(m); }
 
 hipError_t run_tree_attention(const tr_kv &kv, int32_t layer, int32_t H, const TreeDev &tree, const void *d_q,
                               void *d_out, void *ws, hipStream_t st) {
   // standalone op: the split partials sit at the start of the caller's workspace
-  Workspace w;
-  w.part_ml = 0;
-  w.part_acc = align256((size_t)ATTN_MAX_SPLITS * NP * H * 2 * 4);
+  float *ml = (float *)ws;
+  float *acc = ws ? (float *)((unsigned char *)ws + align256((size_t)ATTN_MAX_SPLITS * NP * H * 2 * 4)) : nullptr;
   if (kv.dtype == TR_BF16)
-    return attention_dispatch<bf16_t>(kv, layer, H, tree, tree.n_nodes, (const bf16_t *)d_q, (bf16_t *)d_out, &w,
-                                      (unsigned char *)ws, st);
-  return attention_dispatch<float>(kv, layer, H, tree, tree.n_nodes, (const float *)d_q, (float *)d_out, nullptr,
-                                   (unsigned char *)ws, st);
+    return attention_dispatch<bf16_t>(kv, layer, H, tree, tree.n_nodes, (const bf16_t *)d_q, (bf16_t *)d_out, 0, ml,
+                                      acc, st);
+  return attention_dispatch<float>(kv, layer, H, tree, tree.n_nodes, (const float *)d_q, (float *)d_out, 0, nullptr,
+                                   nullptr, st);
 }
 
-hipError_t run_linear(const void *x, const void *w, int32_t dtype, int32_t n, int32_t in_f, int32_t out_f, float *y,
-                      hipStream_t st) {
-  if (dtype == TR_BF16) return linear_dispatch<bf16_t>((const bf16_t *)x, (const bf16_t *)w, n, in_f, out_f, y, out_f, 0, st);
-  return linear_dispatch<float>((const float *)x, (const float *)w, n, in_f, out_f, y, out_f, 0, st);
+size_t linear_workspace_bytes(int32_t n, int32_t in_f, int32_t out_f, int32_t splits) {
+  const size_t nt = (size_t)(n + 15) / 16;
+  return align256(nt * 16 * in_f * 2) + align256((size_t)splits * n * out_f * 4);
+}
+
+hipError_t run_linear(const void *x, const void *w, int32_t dtype, int32_t layout, int32_t n, int32_t in_f,
+                      int32_t out_f, int32_t splits, float *y, void *ws, hipStream_t st) {
+  if (layout == TR_PACKED) {
+    const int NT = (n + 15) / 16;
+    bf16_t *frag = (bf16_t *)ws;
+    float *part = (float *)((unsigned char *)ws + align256((size_t)NT * 16 * in_f * 2));
+    hipLaunchKernelGGL(k_rows_to_frag, dim3(NT * 16), dim3(256), 0, st, (const bf16_t *)x, n, in_f, NT, frag);
+    TR_TRY(hipGetLastError());
+    GemmArgs g{};
+    g.a_frag = frag; g.n = n; g.K = in_f;
+    g.seg[0] = GemmSeg{(const bf16_t *)w, out_f / 16};
+    g.n_seg = 1; g.y = splits > 1 ? part : y; g.ldy = out_f; g.splits = splits;
+    g.split_stride = (size_t)n * out_f; g.mode = GEMM_STORE;
+    TR_TRY(launch_gemm_mfma(g, st));
+    if (splits > 1) {
+      const size_t count = (size_t)n * out_f;
+      hipLaunchKernelGGL(k_sum_parts, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, part, splits,
+                         (size_t)n * out_f, count, y);
+      TR_TRY(hipGetLastError());
+    }
+    return hipSuccess;
+  }
+  if (dtype == TR_BF16) return linear_generic<bf16_t>(x, w, n, in_f, out_f, y, out_f, 0, st);
+  return linear_generic<float>(x, w, n, in_f, out_f, y, out_f, 0, st);
 }
 
 } // namespace tr

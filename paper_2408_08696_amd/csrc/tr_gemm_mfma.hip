@@ -1,76 +1,129 @@
-// Weight-streaming skinny GEMM on the matrix cores: y[n, O] = a[n, K] * w[O, K]^T, n <= 128 rows
+// Weight-streaming skinny GEMM on the matrix cores: y[n, O] = a[n, K] * w[O, K]^T with n <= 128 rows
 // (the tree nodes), bf16 operands, float32 accumulation.  Every weight byte is read from HBM exactly
-// once per call; the kernel is bound by that stream, the MFMA work (2*n flop per weight element)
-// only has to keep up.
+// once per call; the kernel is bound by that stream, the MFMA work (2*n flop per weight element) only
+// has to keep up.
 //
-// Mapping.  One workgroup owns 16 output features; its WAVES wavefronts split K between them in
-// blocks of 128 and reduce through LDS at the end, so no partial sums ever leave the CU.
-// v_mfma_f32_16x16x32_bf16 computes D[16 outs][16 rows] += W[16][32] * A^T[32][16]:
-//   lane l holds W[o0 + l%16][8 consecutive k of group l/16]   (A operand)
-//        and     A[r0 + l%16][the same 8 k]                    (B operand)
-//   D: lane l holds outs o0 + 4*(l/16) .. +3 for row r0 + l%16.
-// The contraction index may be permuted freely as long as both operands agree, so within a block
-// of 128 k lane group g takes the contiguous 64 bytes k0+32g .. k0+32g+31 (four 16-byte loads that
-// feed four MFMA steps): a wave reads 16 rows x 256 contiguous bytes per block from both operands.
+// Operand layouts.  v_mfma_f32_16x16x32_bf16 computes D[16 x 16] += A[16 x 32] * B[32 x 16] where lane l
+// supplies A[l%16][8*(l/16) .. +7] and B[8*(l/16) .. +7][l%16] as one 16-byte register group, and receives
+// D[4*(l/16) .. +3][l%16].  Both operands are therefore stored in memory in "fragment order": a tile of
+// 16 rows x 32 k is 1 KiB, lane l's 16 bytes at offset 16*l, so that one wave-wide 16-byte load is one
+// fully contiguous KiB and lands directly in MFMA operand registers.
+//   weights (packed once by k_pack_weight):   tile (ot, kt) at ((ot * K/32 + kt) * 1 KiB)
+//   activations (written so by their producers): tile (kt, nt) at ((kt * NT + nt) * 1 KiB), NT = ceil(n/16)
+// With A = weight tile and B = activation tile, lane l ends with outputs o0 + 4*(l/16) .. +3 of row
+// 16*nt + l%16.
+//
+// Mapping.  One workgroup owns OT consecutive out-tiles (16*OT output features) and one of `splits`
+// K-ranges; its 8 wavefronts take interleaved k-tiles of that range, keep PF k-steps of loads in flight
+// in registers, and reduce through LDS in a fixed binary tree at the end.  splits > 1 writes one partial
+// result per split (summed in a fixed order by the consumer), so results are run-to-run deterministic.
 #include "tr_kernels.h"
 
 namespace tr {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int GEMM_WAVES = 8;
-constexpr int GEMM_KB = 128; // k per block
+constexpr int GEMM_PF = 4; // k-steps of loads in flight per wave
 
-__device__ inline f32x4 mfma16(const uint4 &a, const uint4 &b, f32x4 c) {
+__device__ inline f32x4 mfma16(const u32x4 &a, const u32x4 &b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-template <int NT, int MODE>
-__global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(const bf16_t *__restrict__ a, const bf16_t *__restrict__ w,
-                                                               const bf16_t *__restrict__ w2, int32_t n, int32_t K,
-                                                               float *__restrict__ y, int32_t ldy,
-                                                               bf16_t *__restrict__ hout) {
-  constexpr int NW = MODE == GEMM_SWIGLU ? 2 : 1;
+// ---------------------------------------------------------------------------------------------
+// one-time repack of a row-major [O, K] bf16 matrix into fragment order
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_pack_weight(const bf16_t *__restrict__ src, int32_t O, int32_t K,
+                                                     uint4 *__restrict__ dst) {
+  const int KT = K / 32;
+  const size_t slot = (size_t)blockIdx.x * 256 + threadIdx.x; // one 16-byte lane slot
+  const size_t total = (size_t)(O / 16) * KT * 64;
+  if (slot >= total) return;
+  const int lane = (int)(slot & 63);
+  const size_t tile = slot >> 6;
+  const int kt = (int)(tile % KT);
+  const int ot = (int)(tile / KT);
+  const int row = ot * 16 + (lane & 15);
+  const int k = kt * 32 + 8 * (lane >> 4);
+  dst[slot] = *reinterpret_cast<const uint4 *>(src + (size_t)row * K + k);
+}
+
+hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t K, hipStream_t st) {
+  const size_t total = (size_t)(O / 16) * (K / 32) * 64;
+  hipLaunchKernelGGL(k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, src, O, K,
+                     reinterpret_cast<uint4 *>(dst));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// the GEMM
+// ---------------------------------------------------------------------------------------------
+template <int NT, int OT, int MODE>
+__global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(GemmArgs g) {
+  // SWIGLU: OT must be 1; "tile 0" is the gate matrix, "tile 1" the up matrix, same out-tile index
+  constexpr int NW = MODE == GEMM_SWIGLU ? 2 : OT;
   extern __shared__ float red[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int r = lane & 15, g = lane >> 4;
-  const int o0 = blockIdx.x * 16;
-  const uint4 *wp = reinterpret_cast<const uint4 *>(w + (size_t)(o0 + r) * K + 32 * g);
-  const uint4 *wp2 = MODE == GEMM_SWIGLU ? reinterpret_cast<const uint4 *>(w2 + (size_t)(o0 + r) * K + 32 * g) : nullptr;
-  const uint4 *ap[NT];
+  const int KT = g.K / 32;
+
+  // which segment (weight matrix) and out-tile does this workgroup own
+  int tile0 = blockIdx.x * OT; // global out-tile index across the concatenated segments
+  const u32x4 *wbase[NW];
+  {
+    int t = tile0, sidx = 0;
+    while (sidx + 1 < g.n_seg && t >= g.seg[sidx].out_tiles) {
+      t -= g.seg[sidx].out_tiles;
+      ++sidx;
+    }
+    const u32x4 *w = reinterpret_cast<const u32x4 *>(g.seg[sidx].w) + (size_t)t * KT * 64 + lane;
+    if (MODE == GEMM_SWIGLU) {
+      wbase[0] = w;
+      wbase[NW - 1] = reinterpret_cast<const u32x4 *>(g.w2) + (size_t)t * KT * 64 + lane;
+    } else {
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    int row = 16 * t + r;
-    row = row < n ? row : n - 1; // rows past n are computed from a valid row and never stored
-    ap[t] = reinterpret_cast<const uint4 *>(a + (size_t)row * K + 32 * g);
+      for (int u = 0; u < NW; ++u) wbase[u] = w + (size_t)u * KT * 64;
+    }
   }
+  const u32x4 *abase = reinterpret_cast<const u32x4 *>(g.a_frag) + lane;
+
+  // this workgroup's K-range and this wave's k-tiles in it: kt = kt0 + wave + 8*i
+  const int split = blockIdx.y;
+  const int per = (KT + g.splits - 1) / g.splits;
+  const int kt0 = split * per;
+  const int kt1 = kt0 + per < KT ? kt0 + per : KT;
+  const int first = kt0 + wave;
+  const int nsteps = first < kt1 ? (kt1 - first + GEMM_WAVES - 1) / GEMM_WAVES : 0;
+
   f32x4 acc[NW][NT];
 #pragma unroll
   for (int u = 0; u < NW; ++u)
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const int nkb = K / GEMM_KB;
-  for (int kb = wave; kb < nkb; kb += GEMM_WAVES) {
-    const int off = kb * (GEMM_KB / 8); // in uint4 units
-    uint4 wv[NW][4], av[NT][4];
+  u32x4 wq[GEMM_PF][NW], aq[GEMM_PF][NT];
+  auto issue = [&](int stage, int step) {
+    const size_t kt = (size_t)(first + step * GEMM_WAVES);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) wv[0][c] = wp[off + c];
-    if (MODE == GEMM_SWIGLU) {
+    for (int u = 0; u < NW; ++u) wq[stage][u] = __builtin_nontemporal_load(wbase[u] + kt * 64);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) wv[NW - 1][c] = wp2[off + c];
+    for (int t = 0; t < NT; ++t) aq[stage][t] = abase[(kt * NT + t) * 64];
+  };
+#pragma unroll
+  for (int j = 0; j < GEMM_PF; ++j)
+    if (j < nsteps) issue(j, j);
+  for (int base = 0; base < nsteps; base += GEMM_PF) {
+#pragma unroll
+    for (int j = 0; j < GEMM_PF; ++j) {
+      if (base + j < nsteps) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int u = 0; u < NW; ++u) acc[u][t] = mfma16(wq[j][u], aq[j][t], acc[u][t]);
+        if (base + j + GEMM_PF < nsteps) issue(j, base + j + GEMM_PF);
+      }
     }
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) av[t][c] = ap[t][off + c];
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int u = 0; u < NW; ++u) acc[u][t] = mfma16(wv[u][c], av[t][c], acc[u][t]);
   }
 
   // cross-wave reduction, a fixed binary tree through LDS: in round h the upper h waves of the
@@ -99,65 +152,73 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(const bf16_t *__r
     __syncthreads();
   }
   if (wave != 0) return;
-  const int o = o0 + 4 * g;
+  const int r = lane & 15, gq = lane >> 4;
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int row = 16 * t + r;
-    if (row >= n) continue;
     if (MODE == GEMM_STORE) {
-      *reinterpret_cast<float4 *>(y + (size_t)row * ldy + o) =
-          float4{acc[0][t][0], acc[0][t][1], acc[0][t][2], acc[0][t][3]};
-    } else if (MODE == GEMM_ADD) {
-      float4 *dst = reinterpret_cast<float4 *>(y + (size_t)row * ldy + o);
-      float4 cur = *dst;
-      cur.x += acc[0][t][0]; cur.y += acc[0][t][1]; cur.z += acc[0][t][2]; cur.w += acc[0][t][3];
-      *dst = cur;
+      if (row >= g.n) continue;
+      float *yb = g.y + (size_t)split * g.split_stride + (size_t)row * g.ldy;
+#pragma unroll
+      for (int u = 0; u < NW; ++u) {
+        const int o = (tile0 + u) * 16 + 4 * gq;
+        *reinterpret_cast<float4 *>(yb + o) = float4{acc[u][t][0], acc[u][t][1], acc[u][t][2], acc[u][t][3]};
+      }
     } else {
+      // h[row, o .. o+3] = bf16(silu(gate) * up), written in fragment order over (k = o, NT row tiles);
+      // rows past n are written as zeros so the consumer's operand tiles are fully defined
       const f32x4 gt = acc[0][t], up = acc[NW - 1][t];
+      const bool live = row < g.n;
       ushort4 hv;
-      hv.x = f32_to_bf16(gt[0] / (1.0f + expf(-gt[0])) * up[0]);
-      hv.y = f32_to_bf16(gt[1] / (1.0f + expf(-gt[1])) * up[1]);
-      hv.z = f32_to_bf16(gt[2] / (1.0f + expf(-gt[2])) * up[2]);
-      hv.w = f32_to_bf16(gt[3] / (1.0f + expf(-gt[3])) * up[3]);
-      *reinterpret_cast<ushort4 *>(hout + (size_t)row * ldy + o) = hv;
+      hv.x = live ? f32_to_bf16(gt[0] / (1.0f + __expf(-gt[0])) * up[0]) : (bf16_t)0;
+      hv.y = live ? f32_to_bf16(gt[1] / (1.0f + __expf(-gt[1])) * up[1]) : (bf16_t)0;
+      hv.z = live ? f32_to_bf16(gt[2] / (1.0f + __expf(-gt[2])) * up[2]) : (bf16_t)0;
+      hv.w = live ? f32_to_bf16(gt[3] / (1.0f + __expf(-gt[3])) * up[3]) : (bf16_t)0;
+      const int o = tile0 * 16 + 4 * gq;                 // k index of the consumer
+      const size_t slot = ((size_t)(o >> 5) * NT + t) * 64 + r + 16 * ((o & 31) >> 3);
+      *reinterpret_cast<ushort4 *>(g.h_frag + slot * 8 + (o & 7)) = hv;
     }
   }
 }
 
 bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O) {
-  return n >= 1 && n <= TR_MAX_NODES && K % GEMM_KB == 0 && O % 16 == 0;
+  return n >= 1 && n <= TR_MAX_NODES && K % 32 == 0 && O % 32 == 0;
 }
 
-template <int NT>
-static hipError_t launch_nt(const bf16_t *a, const bf16_t *w, const bf16_t *w2, int32_t n, int32_t K, int32_t O,
-                            float *y, int32_t ldy, GemmMode mode, bf16_t *hout, hipStream_t st) {
-  const dim3 grid(O / 16), block(GEMM_WAVES * 64);
-  const size_t smem1 = (size_t)(GEMM_WAVES / 2) * NT * 64 * 16;
-  switch (mode) {
-  case GEMM_STORE:
-    hipLaunchKernelGGL((k_gemm_mfma<NT, GEMM_STORE>), grid, block, smem1, st, a, w, w2, n, K, y, ldy, hout);
-    break;
-  case GEMM_ADD:
-    hipLaunchKernelGGL((k_gemm_mfma<NT, GEMM_ADD>), grid, block, smem1, st, a, w, w2, n, K, y, ldy, hout);
-    break;
-  case GEMM_SWIGLU:
-    hipLaunchKernelGGL((k_gemm_mfma<NT, GEMM_SWIGLU>), grid, block, 2 * smem1, st, a, w, w2, n, K, y, ldy, hout);
-    break;
-  }
+template <int NT, int OT, int MODE>
+static hipError_t launch_k(const GemmArgs &g, int total_tiles, hipStream_t st) {
+  constexpr int NW = MODE == GEMM_SWIGLU ? 2 : OT;
+  const size_t smem = (size_t)(GEMM_WAVES / 2) * NW * NT * 64 * 16;
+  hipLaunchKernelGGL((k_gemm_mfma<NT, OT, MODE>), dim3(total_tiles / OT, g.splits), dim3(GEMM_WAVES * 64), smem, st, g);
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_mfma(const bf16_t *a, const bf16_t *w, const bf16_t *w2, int32_t n, int32_t K, int32_t O,
-                            float *y, int32_t ldy, GemmMode mode, bf16_t *hout, hipStream_t st) {
-  switch ((n + 15) / 16) {
-  case 1: return launch_nt<1>(a, w, w2, n, K, O, y, ldy, mode, hout, st);
-  case 2: return launch_nt<2>(a, w, w2, n, K, O, y, ldy, mode, hout, st);
-  case 3: return launch_nt<3>(a, w, w2, n, K, O, y, ldy, mode, hout, st);
-  case 4: return launch_nt<4>(a, w, w2, n, K, O, y, ldy, mode, hout, st);
-  case 5: return launch_nt<5>(a, w, w2, n, K, O, y, ldy, mode, hout, st);
-  case 6: return launch_nt<6>(a, w, w2, n, K, O, y, ldy, mode, hout, st);
-  case 7: return launch_nt<7>(a, w, w2, n, K, O, y, ldy, mode, hout, st);
-  case 8: return launch_nt<8>(a, w, w2, n, K, O, y, ldy, mode, hout, st);
+template <int NT>
+static hipError_t launch_nt(const GemmArgs &g, int total_tiles, int ot, hipStream_t st) {
+  if (g.mode == GEMM_SWIGLU) return launch_k<NT, 1, GEMM_SWIGLU>(g, total_tiles, st);
+  if (ot == 2) return launch_k<NT, 2, GEMM_STORE>(g, total_tiles, st);
+  return launch_k<NT, 1, GEMM_STORE>(g, total_tiles, st);
+}
+
+hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st) {
+  int total = 0;
+  bool even = true;
+  for (int i = 0; i < g.n_seg; ++i) {
+    total += g.seg[i].out_tiles;
+    even = even && (g.seg[i].out_tiles % 2 == 0);
+  }
+  // two out-tiles per workgroup halve the activation re-reads; keep one when that would leave
+  // fewer workgroups than compute units
+  const int ot = (g.mode != GEMM_SWIGLU && even && (total / 2) * g.splits >= 256) ? 2 : 1;
+  switch ((g.n + 15) / 16) {
+  case 1: return launch_nt<1>(g, total, ot, st);
+  case 2: return launch_nt<2>(g, total, ot, st);
+  case 3: return launch_nt<3>(g, total, ot, st);
+  case 4: return launch_nt<4>(g, total, ot, st);
+  case 5: return launch_nt<5>(g, total, ot, st);
+  case 6: return launch_nt<6>(g, total, ot, st);
+  case 7: return launch_nt<7>(g, total, ot, st);
+  case 8: return launch_nt<8>(g, total, ot, st);
   }
   return hipErrorInvalidValue;
 }

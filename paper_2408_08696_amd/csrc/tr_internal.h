@@ -70,12 +70,42 @@ struct Workspace {
   size_t logits;   // float  [NP, V]            used when the caller passes no logits buffer
   size_t part_ml;  // float  [SPLITS, NP, H, 2] attention split partials: running max, sum
   size_t part_acc; // float  [SPLITS, NP, H, hd]
+  size_t ypart;    // float  [GEMM_MAX_SPLITS, NP, d] K-split partial sums of o_proj / down_proj
   size_t total;
 };
 constexpr int NP = TR_MAX_NODES;
 constexpr int ATTN_MAX_SPLITS = 16;
+constexpr int GEMM_MAX_SPLITS = 4;
 
 Workspace plan_workspace(const tr_model &m);
+
+// ---------------------------------------------------------------------------------------------
+// optional per-kernel-class event timing
+// ---------------------------------------------------------------------------------------------
+enum ProfCat { PC_BUILD = 0, PC_EMBED, PC_NORM, PC_QKV, PC_ROPE, PC_ATTN, PC_OPROJ, PC_GATEUP, PC_DOWN, PC_LMHEAD,
+               PC_TOPK, PC_ACCEPT, PC_COUNT };
+struct Profiler {
+  static constexpr int MAX_PAIRS = 8192;
+  hipEvent_t *ev = nullptr; // 2 * MAX_PAIRS
+  int8_t *cat = nullptr;    // MAX_PAIRS
+  int used = 0;
+  bool enabled = false;
+};
+struct ProfScope {
+  Profiler *p;
+  hipStream_t st;
+  int slot;
+  ProfScope(Profiler *prof, ProfCat c, hipStream_t s) : p(prof), st(s), slot(-1) {
+    if (p != nullptr && p->enabled && p->used < Profiler::MAX_PAIRS) {
+      slot = p->used++;
+      p->cat[slot] = (int8_t)c;
+      (void)hipEventRecord(p->ev[2 * slot], st);
+    }
+  }
+  ~ProfScope() {
+    if (slot >= 0) (void)hipEventRecord(p->ev[2 * slot + 1], st);
+  }
+};
 
 } // namespace tr
 
@@ -88,6 +118,7 @@ struct tr_ctx {
   void *d_tree_blob;     // backing store of both trees
   int32_t *d_step_L;     // committed length at the start of the current accept/update
   int32_t h_depth[TR_MAX_NODES];
+  tr::Profiler prof;
 };
 
 namespace tr {
@@ -104,10 +135,12 @@ hipError_t launch_advance_len(int32_t *d_len, int32_t by, hipStream_t s);
 // --- forward pass (tr_forward.hip) -----------------------------------------------------------------
 // Runs rows `tokens` through the model.  `write_logits` may be NULL (no LM head).
 hipError_t run_forward(const tr_model &m, const tr_kv &kv, const TreeDev &tree, int32_t n,
-                       const int32_t *d_tokens, float *write_logits, void *ws, hipStream_t s);
+                       const int32_t *d_tokens, float *write_logits, void *ws, Profiler *prof, hipStream_t s);
 hipError_t run_tree_attention(const tr_kv &kv, int32_t layer, int32_t H, const TreeDev &tree,
                               const void *d_q, void *d_out, void *ws, hipStream_t s);
-hipError_t run_linear(const void *x, const void *w, int32_t dtype, int32_t n, int32_t in_f,
-                      int32_t out_f, float *y, hipStream_t s);
+size_t linear_workspace_bytes(int32_t n, int32_t in_f, int32_t out_f, int32_t splits);
+hipError_t run_linear(const void *x, const void *w, int32_t dtype, int32_t layout, int32_t n, int32_t in_f,
+                      int32_t out_f, int32_t splits, float *y, void *ws, hipStream_t s);
+bool model_layout_ok(const tr_model &m);
 
 } // namespace tr

@@ -4,22 +4,47 @@
 
 namespace tr {
 
-enum GemmMode { GEMM_STORE = 0, GEMM_ADD = 1, GEMM_SWIGLU = 2 };
+enum GemmMode { GEMM_STORE = 0, GEMM_SWIGLU = 2 };
 
-// y[n, O] = a[n, K] * w[O, K]^T with bf16 operands and float32 accumulation.
-//   GEMM_STORE : y[r*ldy + o]  = acc
-//   GEMM_ADD   : y[r*ldy + o] += acc                       (residual add, one owner per element)
-//   GEMM_SWIGLU: hout[r*ldy + o] = bf16(silu(acc_w) * acc_w2)   (two weight matrices, y unused)
-// Rows of `a` are read up to index n-1 only.
+// Fragment order (see tr_gemm_mfma.hip): a tile of 16 rows x 32 k is 64 lane slots of 8 bf16;
+// element (row r, k) of an operand with T row tiles lives in tile (k/32, r/16) at lane slot
+// (r%16) + 16*((k%32)/8), element k%8.  Weights use tile index (r/16) * (K/32) + k/32 instead.
+__host__ __device__ inline size_t act_frag_index(int r, int k, int row_tiles) {
+  return ((((size_t)(k >> 5) * row_tiles + (r >> 4)) * 64) + (r & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7);
+}
+
+struct GemmSeg {
+  const bf16_t *w;   // packed weight matrix
+  int32_t out_tiles; // its out_features / 16
+};
+
+// y[n, O] = a[n, K] * W^T over the concatenation of up to three weight matrices (out-feature axis).
+//   GEMM_STORE : y[split][row * ldy + o] = partial sum of that K-split (float32, row-major)
+//   GEMM_SWIGLU: h_frag = bf16(silu(a W_gate^T) * (a W_up^T)) in fragment order over (k = o);
+//                seg[0] = gate, w2 = up, splits must be 1
+struct GemmArgs {
+  const bf16_t *a_frag; // activations, fragment order, ceil(n/16) row tiles
+  int32_t n, K;
+  GemmSeg seg[3];
+  int32_t n_seg;
+  const bf16_t *w2;
+  float *y;
+  int32_t ldy;
+  int32_t splits;
+  size_t split_stride; // floats between consecutive partial results
+  bf16_t *h_frag;
+  int32_t mode;
+};
+
 bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O);
-hipError_t launch_gemm_mfma(const bf16_t *a, const bf16_t *w, const bf16_t *w2, int32_t n, int32_t K, int32_t O,
-                            float *y, int32_t ldy, GemmMode mode, bf16_t *hout, hipStream_t st);
+hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st);
+hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t K, hipStream_t st);
 
 // Tree attention for head_dim 128, bf16 K/V/Q, split over the key axis with a merge pass.
 // len_bound: host upper bound of L + n (sizes the split count only).
 bool attn_mfma_supported(int32_t hd, int32_t n);
 hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                             int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t len_bound, float *part_ml,
-                            float *part_acc, bf16_t *out, hipStream_t st);
+                            float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st);
 
 } // namespace tr

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libtr.so")
 TR_MAX_NODES, TR_MAX_LAYERS, TR_MAX_K = 128, 32, 32
 TR_OK, TR_EINVAL, TR_ETEMPLATE, TR_ENOMEM, TR_EHIP, TR_ECAPACITY, TR_ESTATE = 0, -1, -2, -3, -4, -5, -6
 TR_F32, TR_BF16 = 0, 1
+TR_ROW_MAJOR, TR_PACKED = 0, 1
 DTYPES = {"f32": TR_F32, "bf16": TR_BF16}
 
 
@@ -32,7 +33,7 @@ class Layer(C.Structure):
 
 
 class Model(C.Structure):
-    _fields_ = [("dtype", C.c_int32), ("n_layers", C.c_int32), ("d_model", C.c_int32),
+    _fields_ = [("dtype", C.c_int32), ("layout", C.c_int32), ("n_layers", C.c_int32), ("d_model", C.c_int32),
                 ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("rms_eps", C.c_float),
                 ("rope_theta", C.c_float), ("embed", C.c_void_p), ("layers", C.POINTER(Layer)),
@@ -49,6 +50,10 @@ class StepOut(C.Structure):
     _fields_ = [("n_accepted", C.c_int32), ("n_emitted", C.c_int32), ("winner", C.c_int32),
                 ("next_root", C.c_int32), ("kv_len", C.c_int32),
                 ("path", C.c_int32 * TR_MAX_LAYERS), ("emitted", C.c_int32 * TR_MAX_LAYERS)]
+
+
+class ProfileEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 24), ("launches", C.c_int32), ("ms", C.c_double)]
 
 
 STEP_OUT_INTS = C.sizeof(StepOut) // 4
@@ -70,8 +75,11 @@ _SIGS = {
     "tr_op_matrix_update": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "tr_op_tree_attention": [C.c_void_p, C.POINTER(KV), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                              C.c_void_p, C.c_size_t, C.c_void_p],
-    "tr_op_linear": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
-                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
+    "tr_op_linear": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                     C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
+    "tr_pack_weight": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
+    "tr_profile_enable": [C.c_void_p, C.c_int32],
+    "tr_profile_read": [C.c_void_p, C.POINTER(ProfileEntry), C.c_int32, C.POINTER(C.c_int32)],
 }
 EXPORTS = tuple(_SIGS) + ("tr_strerror",)
 
@@ -176,6 +184,15 @@ class Context:
         _check(lib().tr_prefill(self._h, C.byref(model.c), C.byref(kv.c), _ptr(d_tokens), d_tokens.numel(),
                                 _ptr(ws), ws.numel() * ws.element_size(), _stream()), "tr_prefill")
 
+    def profile_enable(self, on: bool) -> None:
+        _check(lib().tr_profile_enable(self._h, 1 if on else 0), "tr_profile_enable")
+
+    def profile_read(self) -> dict:
+        arr = (ProfileEntry * 32)()
+        n = C.c_int32()
+        _check(lib().tr_profile_read(self._h, arr, 32, C.byref(n)), "tr_profile_read")
+        return {arr[i].name.decode(): (arr[i].launches, arr[i].ms) for i in range(n.value)}
+
     def op_topk(self, d_logits, d_topk) -> None:
         import torch
         dt = TR_BF16 if d_logits.dtype == torch.bfloat16 else TR_F32
@@ -190,28 +207,56 @@ class Context:
                                           _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                                           _stream()), "tr_op_tree_attention")
 
-    def op_linear(self, d_x, d_w, d_y, ws=None) -> None:
+    def op_linear(self, d_x, d_w, d_y, ws=None, packed: bool = False, splits: int = 1) -> None:
+        """d_w: [out_f, in_f] row-major, or the packed buffer of the same logical shape."""
         import torch
         dt = TR_BF16 if d_x.dtype == torch.bfloat16 else TR_F32
-        _check(lib().tr_op_linear(self._h, _ptr(d_x), _ptr(d_w), dt, d_x.shape[0], d_x.shape[1], d_w.shape[0],
-                                  _ptr(d_y), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
-                                  _stream()), "tr_op_linear")
+        _check(lib().tr_op_linear(self._h, _ptr(d_x), _ptr(d_w), dt, TR_PACKED if packed else TR_ROW_MAJOR,
+                                  d_x.shape[0], d_x.shape[1], d_w.shape[0], splits, _ptr(d_y), _ptr(ws),
+                                  0 if ws is None else ws.numel() * ws.element_size(), _stream()), "tr_op_linear")
+
+
+def pack_weight(w):
+    """Packed copy of a row-major bf16 [out_f, in_f] device tensor (same shape tag, packed bytes)."""
+    import torch
+    assert w.dtype == torch.bfloat16 and w.is_contiguous() and w.dim() == 2
+    out = torch.empty_like(w)
+    _check(lib().tr_pack_weight(w.data_ptr(), out.data_ptr(), w.shape[0], w.shape[1], _stream()), "tr_pack_weight")
+    return out
+
+
+def can_pack(shape) -> bool:
+    hq, hk = shape.n_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    return shape.dtype == "bf16" and all(v % 32 == 0 for v in (shape.d_model, shape.d_ffn, hq, hk, shape.vocab))
 
 
 class ModelDesc:
     """tr_model over torch tensors (kept alive here).  `weights` has the layout of
-    synth.make_weights; `shape` carries the dimensions."""
+    synth.make_weights; `shape` carries the dimensions.  With pack=True (default where the shape
+    allows it) every projection matrix and the LM head are repacked once into the MFMA operand
+    order; the row-major originals are not referenced afterwards."""
 
-    def __init__(self, shape, weights: dict):
+    MATS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+    def __init__(self, shape, weights: dict, pack: Optional[bool] = None):
+        if pack is None:
+            pack = can_pack(shape)
+        self.packed = bool(pack)
+        if pack:
+            weights = {"embed": weights["embed"], "final_norm": weights["final_norm"],
+                       "lm_head": pack_weight(weights["lm_head"]),
+                       "layers": [{k: (pack_weight(v) if k in self.MATS else v) for k, v in lw.items()}
+                                  for lw in weights["layers"]]}
         self.weights = weights
         n = shape.n_layers
         self._layers = (Layer * n)()
         for l, lw in enumerate(weights["layers"]):
             for name, _ in Layer._fields_:
                 setattr(self._layers[l], name, lw[name].data_ptr())
-        self.c = Model(DTYPES[shape.dtype], n, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
-                       shape.d_ffn, shape.vocab, shape.rms_eps, shape.rope_theta, weights["embed"].data_ptr(),
-                       self._layers, weights["final_norm"].data_ptr(), weights["lm_head"].data_ptr())
+        self.c = Model(DTYPES[shape.dtype], TR_PACKED if pack else TR_ROW_MAJOR, n, shape.d_model, shape.n_heads,
+                       shape.n_kv_heads, shape.head_dim, shape.d_ffn, shape.vocab, shape.rms_eps, shape.rope_theta,
+                       weights["embed"].data_ptr(), self._layers, weights["final_norm"].data_ptr(),
+                       weights["lm_head"].data_ptr())
 
 
 class KVDesc:
@@ -237,11 +282,11 @@ class Engine:
     `step()` issues the three calls of a decode step on the current stream."""
 
     def __init__(self, shape, weights: dict, template, k: int = 8, capacity: int = 2048, device="cuda",
-                 keep_logits: bool = True):
+                 keep_logits: bool = True, pack: Optional[bool] = None, model: Optional[ModelDesc] = None):
         import torch
         self.shape, self.k = shape, k
         self.ctx = Context(shape.vocab, k, template.parent, template.rank, template.n_layers)
-        self.model = ModelDesc(shape, weights)
+        self.model = model if model is not None else ModelDesc(shape, weights, pack)
         self.kv = KVDesc(shape, capacity, device)
         n = template.n_nodes
         self.n_nodes = n

@@ -63,14 +63,19 @@ def test_tiny_fp32_free_running(tmpl_name):
 
 @pytest.mark.parametrize("shape_name,tmpl_name", [("tiny_bf16", "tree80"), ("tiny_gqa_bf16", "tree80"),
                                                   ("tiny_bf16", "tree81"), ("tiny_bf16", "wide128"),
-                                                  ("tiny_bf16", "single"), ("tiny", "tree80")])
+                                                  ("tiny_bf16", "single"), ("tiny", "tree80"),
+                                                  ("tiny_odd_bf16", "tree80"), ("tiny_bf16:rowmajor", "tree15")])
 def test_small_shapes_lockstep(shape_name, tmpl_name):
     require_gpu()
+    pack = None
+    if shape_name.endswith(":rowmajor"):
+        shape_name, pack = shape_name.split(":")[0], False    # bf16 through the generic kernels
     sh = synth.SHAPES[shape_name]
     tmpl = synth.TEMPLATES[tmpl_name]()
     w = synth.make_weights(sh, seed=1)
     prompt = synth.zipf_prompt(sh.vocab, 150, seed=3, ngram=8).tolist()
-    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=512)
+    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=512, pack=pack)
+    assert eng.model.packed == (tr.can_pack(sh) if pack is None else pack)
     abs_tol = 1e-4 if sh.dtype == "f32" else None
     stats, _ = lockstep(eng, sh, synth.weights_to_numpy(w), tmpl, prompt, 6, synth.init_matrix(sh.vocab, K),
                         abs_tol=abs_tol, label=f"{shape_name}/{tmpl_name}")
@@ -114,18 +119,43 @@ def test_capacity_is_checked_on_the_host():
     assert e.value.status == tr.TR_ECAPACITY
 
 
-@pytest.mark.parametrize("n,K_,O_", [(80, 4096, 4096), (80, 11008, 4096), (81, 4096, 1024), (1, 4096, 512),
-                                     (128, 512, 2048), (16, 256, 64), (80, 1024, 32000)])
-def test_linear_bf16_matches_oracle_matmul(n, K_, O_):
-    """The projection kernel alone against a float64 matrix product of the same bf16 values."""
+@pytest.mark.parametrize("n,K_,O_,splits", [(80, 4096, 4096, 2), (80, 11008, 4096, 2), (81, 4096, 1024, 4),
+                                            (1, 4096, 512, 1), (128, 512, 2048, 1), (16, 256, 64, 1),
+                                            (80, 1024, 32000, 1), (80, 4096, 12288, 1), (37, 96, 32, 3)])
+def test_linear_bf16_packed_matches_oracle_matmul(n, K_, O_, splits):
+    """The projection kernel alone (packed weights, MFMA) against a float64 matrix product of the
+    same bf16 values; also checks the repack kernel, since a misplaced element would show here."""
     require_gpu()
-    say("linear", n, K_, O_)
+    say("linear packed", n, K_, O_, splits)
     x = synth.normal_tensor((n, K_), 1.0, seed=n + K_, dtype=torch.bfloat16)
     w = synth.uniform_tensor((O_, K_), float(np.sqrt(3.0 / K_)), seed=5, tensor_id=O_, dtype=torch.bfloat16)
     ctx = tr.Context(16, 8, [-1], [-1], 1)
     y = torch.zeros(n, O_, dtype=torch.float32, device="cuda")
-    ctx.op_linear(x.cuda(), w.cuda(), y)
+    ws = torch.empty(((n + 15) // 16 * 16 * K_ * 2 + 512 + splits * n * O_ * 4 + 512), dtype=torch.uint8, device="cuda")
+    wp = tr.pack_weight(w.cuda())
+    ctx.op_linear(x.cuda(), wp, y, ws, packed=True, splits=splits)
     ref = x.double().numpy() @ w.double().numpy().T
     err = np.abs(y.cpu().numpy() - ref).max()
     say("max err", err)
     assert err < 2e-5 * np.sqrt(K_)                           # fp32 accumulation of K products of O(1/sqrt(K))
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_linear_generic_matches_oracle_matmul(dtype):
+    require_gpu()
+    n, K_, O_ = 45, 344, 130
+    x = synth.normal_tensor((n, K_), 1.0, seed=1, dtype=dtype)
+    w = synth.uniform_tensor((O_, K_), float(np.sqrt(3.0 / K_)), seed=5, tensor_id=3, dtype=dtype)
+    ctx = tr.Context(16, 8, [-1], [-1], 1)
+    y = torch.zeros(n, O_, dtype=torch.float32, device="cuda")
+    ctx.op_linear(x.cuda(), w.cuda(), y)
+    ref = x.double().numpy() @ w.double().numpy().T
+    assert np.abs(y.cpu().numpy() - ref).max() < 2e-5 * np.sqrt(K_)
+
+
+def test_pack_rejects_bad_sizes():
+    require_gpu()
+    w = torch.zeros(48, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(tr.TRError) as e:
+        tr.pack_weight(w)                                      # 48 is not a multiple of 32
+    assert e.value.status == tr.TR_EINVAL
