@@ -108,17 +108,23 @@ typedef struct {
 } tr_model;
 
 /*
- * KV cache, owned by the caller.  Positions 0..*d_len-1 are committed (the content so far);
- * tr_verify_forward additionally writes the N tree nodes' keys/values at positions
- * *d_len .. *d_len+N-1, and tr_accept_and_update moves the accepted ones to the front of that
- * range.  Layout (element type dtype):
- *   k: [n_layers][n_kv_heads][capacity][head_dim]
- *   v: [n_layers][n_kv_heads][head_dim][capacity]      (position-contiguous, i.e. transposed)
+ * KV cache, owned by the caller, zero-initialised by the caller before first use (stale slots are
+ * multiplied by exact zeros, so they must hold finite values).  Positions 0..*d_len-1 are committed
+ * (the content so far); tr_verify_forward additionally writes the N tree nodes' keys/values at
+ * positions *d_len .. *d_len+N-1, and tr_accept_and_update moves the accepted ones to the front of
+ * that range.  Both k and v are [n_layers][n_kv_heads] blocks of capacity * head_dim elements of type
+ * dtype; inside a block, element (position p, feature d) sits at
+ *   TR_KV_PLAIN : k: p * head_dim + d            v: d * capacity + p   (position-contiguous)
+ *   TR_KV_TILED : bf16, head_dim 128, capacity % 32 == 0 only — the operand order of the MI355X
+ *                 matrix cores, required by the fast attention kernel:
+ *                 k: ((p/16)*4 + d/32)*512 + ((p%16) + 16*((d%32)/8))*8 + d%8
+ *                 v: ((p/32)*8 + d/16)*512 + ((d%16) + 16*((p%16)/4))*8 + ((p/16)%2)*4 + p%4
  * len_bound is a host-side upper bound of *d_len kept by the library so that capacity can be
  * checked without reading the device: set both to the same value when (re)initialising.
  */
+typedef enum { TR_KV_PLAIN = 0, TR_KV_TILED = 1 } tr_kv_layout;
 typedef struct {
-  int32_t dtype, n_layers, n_kv_heads, head_dim, capacity;
+  int32_t dtype, layout, n_layers, n_kv_heads, head_dim, capacity;
   void *k;           /* [device] */
   void *v;           /* [device] */
   int32_t *d_len;    /* [device] one int32: committed length L */

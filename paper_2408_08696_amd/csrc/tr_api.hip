@@ -64,6 +64,9 @@ tr_status check_kv(const tr_kv *kv) {
     return TR_EINVAL;
   if (kv->k == nullptr || kv->v == nullptr || kv->d_len == nullptr) return TR_EINVAL;
   if (kv->len_bound < 0) return TR_EINVAL;
+  if (kv->layout != TR_KV_PLAIN && kv->layout != TR_KV_TILED) return TR_EINVAL;
+  if (kv->layout == TR_KV_TILED && (kv->dtype != TR_BF16 || kv->head_dim != 128 || kv->capacity % 32 != 0))
+    return TR_EINVAL;
   return TR_OK;
 }
 

@@ -1,14 +1,244 @@
-// Tree attention on the matrix cores (head_dim 128, bf16).  Placeholder: not enabled yet, the
-// generic kernel serves every shape.
+// Tree attention on the matrix cores (Section 2.2 "Tree Attention"): head_dim 128, bf16 Q/K/V, float32
+// softmax statistics and accumulators.  HBM-bound: every K/V byte of the head is read once per call.
+//
+// Grid (head, split): a workgroup owns one query head and one contiguous range of 32-key tiles; its waves
+// own one tile of 16 tree nodes each, so no cross-wave reduction is needed.  K and V tiles are staged
+// through LDS (double buffered, one barrier per tile) and shared by the waves.
+//
+// Everything is computed transposed so that no value ever changes lanes between the two contractions:
+//   S^T[key][node] = K[key][:] . Q[node][:]      A = K tile (16 keys x 32 d), B = Q^T; lane l receives
+//                                                keys 4*(l/16) .. +3 of node l%16
+//   O^T[d][node]  += V^T[d][key] * P^T[key][node] A = V^T tile (16 d x 32 keys), B = P^T built in place from
+//                                                the lane's own 8 probabilities (two 16-key S^T tiles)
+// The KV cache is kept in exactly these operand orders (TR_KV_TILED, see kv_k_index / kv_v_index), so a
+// tile is one contiguous 8 KiB block in memory and an LDS read of 16 bytes per lane is an MFMA operand.
+//
+// Mask: key position p is visible to node i when p < L (committed prefix), or L <= p < L + N and bit
+// p - L of the node's ancestor mask is set.  Invisible keys get probability exactly 0.
+// With more than one split, each writes (max, sum, unnormalised O) per node and k_attn_merge combines
+// them in split order.
 #include "tr_kernels.h"
 
 namespace tr {
 
-bool attn_mfma_supported(int32_t, int32_t) { return false; }
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-hipError_t launch_attn_mfma(const bf16_t *, const bf16_t *, const bf16_t *, int32_t, int32_t, int32_t, int32_t,
-                            const uint64_t *, const int32_t *, int32_t, float *, float *, bf16_t *, int32_t, hipStream_t) {
-  return hipErrorNotSupported;
+__device__ inline f32x4 mfma16a(const u32x4 &a, const u32x4 &b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+constexpr int ATT_TILE_BYTES = 16384; // 32 keys: K 8 KiB + V 8 KiB
+constexpr float NEG_BIG = -1e30f;
+
+template <int NT>
+__global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict__ q, const bf16_t *__restrict__ Kl,
+                                                       const bf16_t *__restrict__ Vl, int32_t H, int32_t Hkv,
+                                                       int32_t cap, int32_t n, const uint64_t *__restrict__ anc,
+                                                       const int32_t *__restrict__ d_len, int32_t nsplit,
+                                                       float *__restrict__ part_ml, float *__restrict__ part_acc,
+                                                       bf16_t *__restrict__ out, int32_t out_row_tiles) {
+  constexpr int THREADS = NT * 64;
+  constexpr int SLOTS = ATT_TILE_BYTES / 16;                 // 16-byte slots per tile
+  constexpr int PER_THREAD = (SLOTS + THREADS - 1) / THREADS;
+  __shared__ u32x4 lds[2][SLOTS];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r = lane & 15, g = lane >> 4;
+  const int h = blockIdx.x, split = blockIdx.y;
+  const int hk = h / (H / Hkv);
+  const int L = *d_len;
+  const int total = L + n;
+  const int n_tiles = (total + 31) >> 5;
+  const int per = (n_tiles + nsplit - 1) / nsplit;
+  const int t0 = split * per;
+  const int t1 = t0 + per < n_tiles ? t0 + per : n_tiles;
+
+  const int node = wave * 16 + r;
+  const int node_c = node < n ? node : n - 1;
+  // Q^T operand: lane (node r, group g) holds Q[node][32c + 8g .. +7] for d-step c
+  u32x4 qf[4];
+  {
+    const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + ((size_t)node_c * H + h) * 128 + 8 * g);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) qf[c] = qp[c * 4];
+  }
+  const uint64_t a0 = anc[2 * node_c], a1 = anc[2 * node_c + 1];
+
+  const u32x4 *Kh = reinterpret_cast<const u32x4 *>(Kl + (size_t)hk * cap * 128);
+  const u32x4 *Vh = reinterpret_cast<const u32x4 *>(Vl + (size_t)hk * cap * 128);
+
+  f32x4 acc[8];
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = NEG_BIG, lsum = 0.f;
+  const float sc = 0.08838834764831845f * 1.4426950408889634f; // 1/sqrt(128) * log2(e)
+
+  u32x4 stage[PER_THREAD];
+  auto fetch = [&](int tile) {
+    // K tile: 512 slots at Kh + tile*512; V tile: 512 slots at Vh + tile*512
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const int s = tid + i * THREADS;
+      if (s < SLOTS) stage[i] = s < 512 ? Kh[(size_t)tile * 512 + s] : Vh[(size_t)tile * 512 + (s - 512)];
+    }
+  };
+  auto publish = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const int s = tid + i * THREADS;
+      if (s < SLOTS) lds[buf][s] = stage[i];
+    }
+  };
+
+  if (t0 < t1) fetch(t0);
+  for (int t = t0; t < t1; ++t) {
+    const int buf = (t - t0) & 1;
+    publish(buf);
+    __syncthreads();
+    if (t + 1 < t1) fetch(t + 1);
+    const u32x4 *kt = lds[buf];
+    const u32x4 *vt = lds[buf] + 512;
+
+    f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      s0 = mfma16a(kt[c * 64 + lane], qf[c], s0);
+      s1 = mfma16a(kt[(4 + c) * 64 + lane], qf[c], s1);
+    }
+    float x[8];
+    bool vis[8];
+    const int pbase = t * 32 + 4 * g;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int p = pbase + (e >> 2) * 16 + (e & 3);
+      bool v = p < L;
+      if (!v && p < total) {
+        const int j = p - L;
+        v = j < 64 ? ((a0 >> j) & 1ull) : ((a1 >> (j - 64)) & 1ull);
+      }
+      vis[e] = v;
+      const float sv = (e < 4 ? s0[e & 3] : s1[e & 3]) * sc;
+      x[e] = v ? sv : NEG_BIG;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m, mx);
+    const float corr = exp2f(m - m_new);
+    m = m_new;
+    float ps = 0.f;
+    uint32_t pk[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      const float p0 = vis[e] ? exp2f(x[e] - m_new) : 0.f;
+      const float p1 = vis[e + 1] ? exp2f(x[e + 1] - m_new) : 0.f;
+      const bf16_t b0 = f32_to_bf16(p0), b1 = f32_to_bf16(p1);
+      // the sum uses the rounded probabilities, i.e. exactly the weights that multiply V
+      ps += bf16_to_f32(b0) + bf16_to_f32(b1);
+      pk[e >> 1] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+    }
+    lsum = lsum * corr + ps;
+    const u32x4 pf = u32x4{pk[0], pk[1], pk[2], pk[3]};
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      f32x4 a = acc[dt];
+      a[0] *= corr; a[1] *= corr; a[2] *= corr; a[3] *= corr;
+      acc[dt] = mfma16a(vt[dt * 64 + lane], pf, a);
+    }
+  }
+  lsum += __shfl_xor(lsum, 16);
+  lsum += __shfl_xor(lsum, 32);
+  if (node >= n) return;
+
+  if (nsplit == 1) {
+    const float inv = 1.0f / lsum;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      const int d = 16 * dt + 4 * g;
+      ushort4 o;
+      o.x = f32_to_bf16(acc[dt][0] * inv); o.y = f32_to_bf16(acc[dt][1] * inv);
+      o.z = f32_to_bf16(acc[dt][2] * inv); o.w = f32_to_bf16(acc[dt][3] * inv);
+      const size_t idx = out_row_tiles > 0 ? act_frag_index(node, h * 128 + d, out_row_tiles)
+                                           : ((size_t)node * H + h) * 128 + d;
+      *reinterpret_cast<ushort4 *>(out + idx) = o;
+    }
+    return;
+  }
+  const size_t row = ((size_t)split * H + h) * NP + node;
+  if (g == 0) {
+    part_ml[row * 2] = m;
+    part_ml[row * 2 + 1] = lsum;
+  }
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt)
+    *reinterpret_cast<float4 *>(part_acc + row * 128 + 16 * dt + 4 * g) =
+        float4{acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]};
+}
+
+// out[node, h, :] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max m); splits without visible keys
+// (l_s == 0) are skipped.  Block (node, head), 128 threads = head_dim.
+__global__ __launch_bounds__(128) void k_attn_merge(const float *__restrict__ part_ml, const float *__restrict__ part_acc,
+                                                    int32_t H, int32_t nsplit, bf16_t *__restrict__ out,
+                                                    int32_t out_row_tiles) {
+  const int node = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
+  float M = NEG_BIG;
+  for (int s = 0; s < nsplit; ++s) {
+    const size_t row = ((size_t)s * H + h) * NP + node;
+    if (part_ml[row * 2 + 1] > 0.f) M = fmaxf(M, part_ml[row * 2]);
+  }
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const size_t row = ((size_t)s * H + h) * NP + node;
+    const float l = part_ml[row * 2 + 1];
+    if (l > 0.f) {
+      const float w = exp2f(part_ml[row * 2] - M);
+      den += w * l;
+      num += w * part_acc[row * 128 + d];
+    }
+  }
+  const size_t idx = out_row_tiles > 0 ? act_frag_index(node, h * 128 + d, out_row_tiles)
+                                       : ((size_t)node * H + h) * 128 + d;
+  out[idx] = f32_to_bf16(num / den);
+}
+
+bool attn_mfma_supported(int32_t hd, int32_t n) { return hd == 128 && n >= 1 && n <= TR_MAX_NODES; }
+
+int attn_choose_splits(int32_t H, int32_t len_bound) {
+  const int tiles = (len_bound + 31) / 32;
+  int s = 1;
+  while (s < ATTN_MAX_SPLITS && H * s < 256 && 2 * s <= tiles) s *= 2;
+  return s;
+}
+
+template <int NT>
+static hipError_t launch_attn_nt(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
+                                 int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t nsplit, float *part_ml,
+                                 float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st) {
+  hipLaunchKernelGGL(k_attn_mfma<NT>, dim3(H, nsplit), dim3(NT * 64), 0, st, q, Kl, Vl, H, Hkv, cap, n, anc, d_len,
+                     nsplit, part_ml, part_acc, out, out_row_tiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
+                            int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t len_bound, float *part_ml,
+                            float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st) {
+  const int nsplit = attn_choose_splits(H, len_bound);
+  hipError_t e = hipErrorInvalidValue;
+  switch ((n + 15) / 16) {
+  case 1: e = launch_attn_nt<1>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 2: e = launch_attn_nt<2>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 3: e = launch_attn_nt<3>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 4: e = launch_attn_nt<4>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 5: e = launch_attn_nt<5>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 6: e = launch_attn_nt<6>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 7: e = launch_attn_nt<7>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 8: e = launch_attn_nt<8>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  }
+  if (e != hipSuccess || nsplit == 1) return e;
+  hipLaunchKernelGGL(k_attn_merge, dim3(n, H), dim3(128), 0, st, part_ml, part_acc, H, nsplit, out, out_row_tiles);
+  return hipGetLastError();
 }
 
 } // namespace tr

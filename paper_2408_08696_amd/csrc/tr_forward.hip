@@ -149,7 +149,7 @@ template <typename T>
 __global__ __launch_bounds__(128) void k_rope_kv(const float *__restrict__ qkv, const float *__restrict__ rope,
                                                  int32_t H, int32_t Hkv, int32_t hd, int32_t cap,
                                                  const int32_t *__restrict__ d_len, T *__restrict__ q,
-                                                 T *__restrict__ Kl, T *__restrict__ Vl) {
+                                                 T *__restrict__ Kl, T *__restrict__ Vl, int32_t tiled) {
   const int n = blockIdx.x, hh = blockIdx.y;
   const int half = hd / 2;
   const int width = (H + 2 * Hkv) * hd;
@@ -164,12 +164,19 @@ __global__ __launch_bounds__(128) void k_rope_kv(const float *__restrict__ qkv, 
         T *dst = q + ((size_t)n * H + hh) * hd;
         dst[i] = ra;
         dst[i + half] = rb;
+      } else if (tiled) {
+        T *dst = Kl + (size_t)(hh - H) * cap * hd;
+        dst[kv_k_index(pos, i)] = ra;
+        dst[kv_k_index(pos, i + half)] = rb;
       } else {
         T *dst = Kl + ((size_t)(hh - H) * cap + pos) * hd;
         dst[i] = ra;
         dst[i + half] = rb;
       }
     }
+  } else if (tiled) {
+    T *dst = Vl + (size_t)(hh - H - Hkv) * hd * cap;
+    for (int i = threadIdx.x; i < hd; i += blockDim.x) dst[kv_v_index(pos, i)] = from_f32<T>(src[i]);
   } else {
     T *dst = Vl + (size_t)(hh - H - Hkv) * hd * cap + pos;
     for (int i = threadIdx.x; i < hd; i += blockDim.x) dst[(size_t)i * cap] = from_f32<T>(src[i]);
@@ -266,7 +273,7 @@ static hipError_t attention_dispatch(const tr_kv &kv, int32_t layer, int32_t H, 
   const size_t lsz = (size_t)kv.n_kv_heads * kv.capacity * kv.head_dim;
   const T *Kl = (const T *)kv.k + (size_t)layer * lsz;
   const T *Vl = (const T *)kv.v + (size_t)layer * lsz;
-  if (sizeof(T) == 2 && attn_mfma_supported(kv.head_dim, n) && part_ml != nullptr) {
+  if (kv.layout == TR_KV_TILED) {
     return launch_attn_mfma((const bf16_t *)q, (const bf16_t *)Kl, (const bf16_t *)Vl, H, kv.n_kv_heads, kv.capacity,
                             n, tree.anc, kv.d_len, kv.len_bound + n, part_ml, part_acc, (bf16_t *)out, out_row_tiles,
                             st);
@@ -318,7 +325,7 @@ static hipError_t forward_generic(const tr_model &m, const tr_kv &kv, const Tree
     {
       ProfScope ps(prof, PC_ROPE, st);
       hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, rope, H, Hkv, hd, kv.capacity,
-                         kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz);
+                         kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, kv.layout);
       TR_TRY(hipGetLastError());
     }
     {
@@ -488,7 +495,7 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
     {
       ProfScope ps(prof, PC_ROPE, st);
       hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, rope, H, Hkv, hd, kv.capacity,
-                         kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz);
+                         kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, kv.layout);
       TR_TRY(hipGetLastError());
     }
     {

@@ -212,7 +212,7 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_accept_update(int32_t *__restr
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_compact_kv(T *__restrict__ K, T *__restrict__ Vt, int32_t cap, int32_t hd,
-                                                    const int32_t *__restrict__ step_L,
+                                                    int32_t tiled, const int32_t *__restrict__ step_L,
                                                     const tr_step_out *__restrict__ out) {
   extern __shared__ unsigned char smem_raw[];
   T *sk = reinterpret_cast<T *>(smem_raw);          // [a+1][hd]
@@ -227,15 +227,15 @@ __global__ __launch_bounds__(256) void k_compact_kv(T *__restrict__ K, T *__rest
   for (int e = threadIdx.x; e < total; e += blockDim.x) {
     const int i = e / hd, d = e - i * hd;
     const int src = L + out->path[i];
-    sk[e] = Kb[(size_t)src * hd + d];
-    sv[e] = Vb[(size_t)d * cap + src];
+    sk[e] = Kb[tiled ? kv_k_index(src, d) : (size_t)src * hd + d];
+    sv[e] = Vb[tiled ? kv_v_index(src, d) : (size_t)d * cap + src];
   }
   __syncthreads();
   for (int e = threadIdx.x; e < total; e += blockDim.x) {
     const int i = e / hd, d = e - i * hd;
     const int dst = L + i;
-    Kb[(size_t)dst * hd + d] = sk[e];
-    Vb[(size_t)d * cap + dst] = sv[e];
+    Kb[tiled ? kv_k_index(dst, d) : (size_t)dst * hd + d] = sk[e];
+    Vb[tiled ? kv_v_index(dst, d) : (size_t)d * cap + dst] = sv[e];
   }
 }
 
@@ -250,10 +250,10 @@ hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t 
   const size_t smem = 2 * (size_t)TR_MAX_LAYERS * kv->head_dim * esz;
   if (kv->dtype == TR_BF16)
     hipLaunchKernelGGL(k_compact_kv<bf16_t>, dim3(blocks), dim3(256), smem, st, (bf16_t *)kv->k, (bf16_t *)kv->v,
-                       kv->capacity, kv->head_dim, c->d_step_L, d_out);
+                       kv->capacity, kv->head_dim, kv->layout, c->d_step_L, d_out);
   else
     hipLaunchKernelGGL(k_compact_kv<float>, dim3(blocks), dim3(256), smem, st, (float *)kv->k, (float *)kv->v,
-                       kv->capacity, kv->head_dim, c->d_step_L, d_out);
+                       kv->capacity, kv->head_dim, kv->layout, c->d_step_L, d_out);
   return hipGetLastError();
 }
 

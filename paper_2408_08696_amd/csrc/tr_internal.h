@@ -36,6 +36,19 @@ template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return f32_to_b
 
 inline size_t dtype_size(int32_t dt) { return dt == TR_BF16 ? 2 : 4; }
 
+// Element offsets inside one (layer, kv head) block of the cache, head_dim 128, TR_KV_TILED.
+// K: 16 positions x 32 d per KiB tile, tiles ordered (pos/16, d/32): the A operand of S^T = K Q^T.
+// V: 16 d x 32 positions per KiB tile, tiles ordered (pos/32, d/16); inside a lane slot the 8 elements
+//    are positions {4g..4g+3} of the first and of the second 16-position half (g = slot/16): the order in
+//    which the S^T accumulators of two consecutive 16-key tiles sit in a lane.
+__host__ __device__ inline size_t kv_k_index(int pos, int d) {
+  return ((size_t)(pos >> 4) * 4 + (d >> 5)) * 512 + ((pos & 15) + 16 * ((d & 31) >> 3)) * 8 + (d & 7);
+}
+__host__ __device__ inline size_t kv_v_index(int pos, int d) {
+  return ((size_t)(pos >> 5) * 8 + (d >> 4)) * 512 + ((d & 15) + 16 * ((pos & 15) >> 2)) * 8 + ((pos >> 4) & 1) * 4 +
+         (pos & 3);
+}
+
 // ---------------------------------------------------------------------------------------------
 // device copy of a tree: node i sits depth[i] below the root and may attend to the tree nodes
 // whose bits are set in anc[i] (its ancestors and itself; 128 bits as two 64-bit words)

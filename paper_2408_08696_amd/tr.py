@@ -19,6 +19,7 @@ TR_MAX_NODES, TR_MAX_LAYERS, TR_MAX_K = 128, 32, 32
 TR_OK, TR_EINVAL, TR_ETEMPLATE, TR_ENOMEM, TR_EHIP, TR_ECAPACITY, TR_ESTATE = 0, -1, -2, -3, -4, -5, -6
 TR_F32, TR_BF16 = 0, 1
 TR_ROW_MAJOR, TR_PACKED = 0, 1
+TR_KV_PLAIN, TR_KV_TILED = 0, 1
 DTYPES = {"f32": TR_F32, "bf16": TR_BF16}
 
 
@@ -41,7 +42,7 @@ class Model(C.Structure):
 
 
 class KV(C.Structure):
-    _fields_ = [("dtype", C.c_int32), ("n_layers", C.c_int32), ("n_kv_heads", C.c_int32),
+    _fields_ = [("dtype", C.c_int32), ("layout", C.c_int32), ("n_layers", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("capacity", C.c_int32), ("k", C.c_void_p),
                 ("v", C.c_void_p), ("d_len", C.c_void_p), ("len_bound", C.c_int32)]
 
@@ -260,17 +261,23 @@ class ModelDesc:
 
 
 class KVDesc:
-    """tr_kv plus the torch tensors behind it.
-    k: [layers, kv_heads, capacity, head_dim]; v: [layers, kv_heads, head_dim, capacity]."""
+    """tr_kv plus the torch tensors behind it (zero-initialised).  Tiled layout (the fast attention
+    kernel's operand order) for bf16 with head_dim 128 unless tiled=False; capacity is rounded up
+    to a multiple of 32.  Plain layout: k [layers, kv_heads, capacity, head_dim],
+    v [layers, kv_heads, head_dim, capacity]."""
 
-    def __init__(self, shape, capacity: int, device="cuda"):
+    def __init__(self, shape, capacity: int, device="cuda", tiled: Optional[bool] = None):
         import torch
         dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        capacity = (capacity + 31) // 32 * 32
+        if tiled is None:
+            tiled = shape.dtype == "bf16" and shape.head_dim == 128
+        self.tiled, self.capacity = bool(tiled), capacity
         self.k = torch.zeros(shape.n_layers, shape.n_kv_heads, capacity, shape.head_dim, dtype=dt, device=device)
         self.v = torch.zeros(shape.n_layers, shape.n_kv_heads, shape.head_dim, capacity, dtype=dt, device=device)
         self.d_len = torch.zeros(1, dtype=torch.int32, device=device)
-        self.c = KV(DTYPES[shape.dtype], shape.n_layers, shape.n_kv_heads, shape.head_dim, capacity,
-                    self.k.data_ptr(), self.v.data_ptr(), self.d_len.data_ptr(), 0)
+        self.c = KV(DTYPES[shape.dtype], TR_KV_TILED if tiled else TR_KV_PLAIN, shape.n_layers, shape.n_kv_heads,
+                    shape.head_dim, capacity, self.k.data_ptr(), self.v.data_ptr(), self.d_len.data_ptr(), 0)
 
     def reset(self, length: int = 0) -> None:
         self.d_len.fill_(length)
@@ -282,12 +289,13 @@ class Engine:
     `step()` issues the three calls of a decode step on the current stream."""
 
     def __init__(self, shape, weights: dict, template, k: int = 8, capacity: int = 2048, device="cuda",
-                 keep_logits: bool = True, pack: Optional[bool] = None, model: Optional[ModelDesc] = None):
+                 keep_logits: bool = True, pack: Optional[bool] = None, model: Optional[ModelDesc] = None,
+                 kv_tiled: Optional[bool] = None):
         import torch
         self.shape, self.k = shape, k
         self.ctx = Context(shape.vocab, k, template.parent, template.rank, template.n_layers)
         self.model = model if model is not None else ModelDesc(shape, weights, pack)
-        self.kv = KVDesc(shape, capacity, device)
+        self.kv = KVDesc(shape, capacity, device, kv_tiled)
         n = template.n_nodes
         self.n_nodes = n
         self.ws = torch.empty(self.ctx.workspace_bytes(self.model), dtype=torch.uint8, device=device)

@@ -79,3 +79,44 @@ def lockstep(eng, sh, w_np, tmpl, prompt, n_steps, M0, k=8, rel_tol=2e-2, abs_to
         stats.append(dict(step=step, max_err=float(err.max()), max_rel=float(np.max(err / scale)), flips=flips,
                           n_emitted=acc.n_accepted + 1))
     return stats, kv
+
+
+# ---- tiled KV layout, restated from include/tr.h (TR_KV_TILED) for test-side encode/decode ----
+def _k_index(p, d):
+    return ((p // 16) * 4 + d // 32) * 512 + ((p % 16) + 16 * ((d % 32) // 8)) * 8 + d % 8
+
+
+def _v_index(p, d):
+    return ((p // 32) * 8 + d // 16) * 512 + ((d % 16) + 16 * ((p % 16) // 4)) * 8 + ((p // 16) % 2) * 4 + p % 4
+
+
+def kv_maps(cap, hd=128):
+    p, d = np.meshgrid(np.arange(cap), np.arange(hd), indexing="ij")
+    return _k_index(p, d), _v_index(p, d)          # [cap, hd] -> flat offset
+
+
+def kv_plain_views(kvdesc):
+    """(k, v) as torch tensors [layers, heads, cap, hd] in natural order, whatever the layout."""
+    L, Hk, cap, hd = kvdesc.k.shape
+    if not kvdesc.tiled:
+        return kvdesc.k, kvdesc.v.permute(0, 1, 3, 2)
+    ki, vi = kv_maps(cap, hd)
+    ki = torch.from_numpy(ki).to(kvdesc.k.device).reshape(-1)
+    vi = torch.from_numpy(vi).to(kvdesc.k.device).reshape(-1)
+    kf = kvdesc.k.reshape(L, Hk, cap * hd)[:, :, ki].reshape(L, Hk, cap, hd)
+    vf = kvdesc.v.reshape(L, Hk, cap * hd)[:, :, vi].reshape(L, Hk, cap, hd)
+    return kf, vf
+
+
+def kv_fill(kvdesc, k_plain, v_plain):
+    """Write natural-order tensors [layers, heads, cap, hd] into the cache in its layout."""
+    L, Hk, cap, hd = kvdesc.k.shape
+    if not kvdesc.tiled:
+        kvdesc.k.copy_(k_plain)
+        kvdesc.v.copy_(v_plain.permute(0, 1, 3, 2))
+        return
+    ki, vi = kv_maps(cap, hd)
+    ki = torch.from_numpy(ki).to(kvdesc.k.device).reshape(-1)
+    vi = torch.from_numpy(vi).to(kvdesc.k.device).reshape(-1)
+    kvdesc.k.reshape(L, Hk, cap * hd)[:, :, ki] = k_plain.reshape(L, Hk, cap * hd)
+    kvdesc.v.reshape(L, Hk, cap * hd)[:, :, vi] = v_plain.reshape(L, Hk, cap * hd)

@@ -5,7 +5,7 @@ import torch
 
 from oracle import tr_oracle as O
 from paper_2408_08696_amd import synth, tr
-from gpu_util import lockstep, oracle_cfg, require_gpu, say, to_gpu
+from gpu_util import kv_fill, kv_plain_views, lockstep, oracle_cfg, require_gpu, say, to_gpu
 from test_oracle_loop import FIXTURE_MIN_GAP, fixture_min_gap
 
 pytestmark = pytest.mark.gpu
@@ -55,8 +55,9 @@ def test_tiny_fp32_free_running(tmpl_name):
         assert 4 * max_err < FIXTURE_MIN_GAP <= fixture_min_gap(0)
     # committed KV equals the oracle's cache (K as stored, V transposed)
     L = kv.len
-    kg = eng.kv.k[:, :, :L, :].permute(0, 2, 1, 3).cpu().numpy()
-    vg = eng.kv.v[:, :, :, :L].permute(0, 3, 1, 2).cpu().numpy()
+    kp, vp = kv_plain_views(eng.kv)
+    kg = kp[:, :, :L, :].permute(0, 2, 1, 3).cpu().numpy()
+    vg = vp[:, :, :L, :].permute(0, 2, 1, 3).cpu().numpy()
     for l in range(sh.n_layers):
         assert np.abs(kg[l] - kv.k[l][:L]).max() < 1e-4 and np.abs(vg[l] - kv.v[l][:L]).max() < 1e-4
 
@@ -97,8 +98,9 @@ def test_prefill_crosses_chunk_boundaries():
     cfg = oracle_cfg(sh)
     kv = O.KVCache(cfg, 400)
     O.prefill(cfg, wn, kv, prompt[:-1])
-    kg = eng.kv.k[:, :, :299, :].permute(0, 2, 1, 3).cpu().numpy()
-    vg = eng.kv.v[:, :, :, :299].permute(0, 3, 1, 2).cpu().numpy()
+    kp, vp = kv_plain_views(eng.kv)
+    kg = kp[:, :, :299, :].permute(0, 2, 1, 3).cpu().numpy()
+    vg = vp[:, :, :299, :].permute(0, 2, 1, 3).cpu().numpy()
     for l in range(sh.n_layers):
         assert np.abs(kg[l] - kv.k[l][:299]).max() < 1e-4
         assert np.abs(vg[l] - kv.v[l][:299]).max() < 1e-4
@@ -109,14 +111,53 @@ def test_capacity_is_checked_on_the_host():
     sh = synth.SHAPES["tiny"]
     w = synth.make_weights(sh, seed=2)
     tmpl = synth.tree15()
-    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=40)
+    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=64)
+    assert eng.kv.capacity == 64
     with pytest.raises(tr.TRError) as e:
-        eng.prefill(list(range(60)))
+        eng.prefill(list(range(80)))
     assert e.value.status == tr.TR_ECAPACITY
-    eng.prefill(list(range(30)))
+    eng.prefill(list(range(55)))
     with pytest.raises(tr.TRError) as e:
-        eng.step()                                            # 29 + 15 > 40
+        eng.step()                                            # 54 + 15 > 64
     assert e.value.status == tr.TR_ECAPACITY
+
+
+@pytest.mark.parametrize("tmpl_name,H,Hkv,L,tiled", [("tree80", 32, 32, 1024, True), ("tree80", 8, 2, 1000, True),
+                                                     ("tree81", 4, 4, 37, True), ("wide128", 4, 1, 300, True),
+                                                     ("single", 8, 8, 513, True), ("tree15", 4, 4, 0, True),
+                                                     ("tree80", 4, 2, 200, False)])
+def test_tree_attention_matches_per_path_attention(tmpl_name, H, Hkv, L, tiled):
+    """One layer of tree attention at the microbenchmark shape (32 heads x 128, prefix 1024, 80
+    nodes, N(0,1) values) and smaller ones: every node must equal plain softmax attention over
+    (prefix, its root-to-node path) computed by the oracle in float64."""
+    require_gpu()
+    say("tree attention", tmpl_name, H, Hkv, L, tiled)
+    t = synth.TEMPLATES[tmpl_name]()
+    tree = O.make_tree(t.parent, t.rank, K)
+    n, hd = t.n_nodes, 128
+    sh = synth.ModelShape("att", 1, H * hd, H, Hkv, hd, 64, 64, "bf16")
+    kv = tr.KVDesc(sh, capacity=L + n + 5, tiled=tiled)
+    kv.reset(L)
+    q = synth.normal_tensor((n, H, hd), 1.0, seed=1, dtype=torch.bfloat16)
+    kp = synth.normal_tensor((1, Hkv, kv.capacity, hd), 1.0, seed=2, dtype=torch.bfloat16)
+    vp = synth.normal_tensor((1, Hkv, kv.capacity, hd), 1.0, seed=3, dtype=torch.bfloat16)
+    kv_fill(kv, kp.cuda(), vp.cuda())
+    ctx = tr.Context(64, K, t.parent, t.rank, t.n_layers)
+    out = torch.zeros(n, H, hd, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(16 * 128 * H * (2 + hd) * 4 + 4096, dtype=torch.uint8, device="cuda")
+    ctx.op_tree_attention(kv, 0, H, q.cuda(), out, ws)
+    got = out.float().cpu().numpy()
+    qn = q.double().numpy()
+    kn = kp[0].double().numpy().transpose(1, 0, 2)             # [cap, Hkv, hd]
+    vn = vp[0].double().numpy().transpose(1, 0, 2)
+    worst = 0.0
+    for i in range(n):
+        idx = list(range(L)) + [L + j for j in tree.paths[i]]
+        ref = O._attend(qn[i], kn[idx], vn[idx], H // Hkv)
+        err = np.abs(got[i] - ref).max()
+        worst = max(worst, err / np.abs(ref).max())
+        assert err <= 2e-2 * np.abs(ref).max(), (i, err)
+    say("worst relative error", worst)
 
 
 @pytest.mark.parametrize("n,K_,O_,splits", [(80, 4096, 4096, 2), (80, 11008, 4096, 2), (81, 4096, 1024, 4),

@@ -8,7 +8,7 @@ import torch
 
 from oracle import tr_oracle as O
 from paper_2408_08696_amd import synth, tr
-from gpu_util import require_gpu, say
+from gpu_util import kv_fill, kv_plain_views, require_gpu, say
 
 pytestmark = pytest.mark.gpu
 K = 8
@@ -122,22 +122,26 @@ def test_update_example_on_gpu(golden):
         assert M[tok].tolist() == [int(x) for x in g[f"expect_both {tok}"][0]]
 
 
-def _run_accept(t, S, topk, V=64, L=10, hd=32, layers=2, heads=2):
-    """Calls tr_accept_and_update on a small f32 cache whose tree rows are tagged with their node
-    index, returns (StepOut, M, k-cache, v-cache)."""
-    sh = synth.ModelShape("acc", layers, 64, heads, heads, hd, 64, V, "f32")
+def _run_accept(t, S, topk, V=64, L=10, hd=32, layers=2, heads=2, dtype="f32"):
+    """Calls tr_accept_and_update on a small cache whose tree rows are tagged with their node
+    index, returns (StepOut, M, k-cache, v-cache) with the caches in natural [.., pos, hd] order."""
+    sh = synth.ModelShape("acc", layers, 64, heads, heads, hd, 64, V, dtype)
     ctx = tr.Context(V, topk.shape[1], t.parent, t.rank, t.n_layers)
     kv = tr.KVDesc(sh, capacity=L + t.n_nodes + 4)
     kv.reset(L)
     n = t.n_nodes
     tag = torch.arange(n, dtype=torch.float32, device="cuda") + 100.0
-    kv.k[:, :, L:L + n, :] = tag[None, None, :, None]
-    kv.v[:, :, :, L:L + n] = -tag[None, None, None, :]
+    kp = torch.zeros(layers, heads, kv.capacity, hd, dtype=kv.k.dtype, device="cuda")
+    vp = torch.zeros_like(kp)
+    kp[:, :, L:L + n, :] = tag[None, None, :, None].to(kp.dtype)
+    vp[:, :, L:L + n, :] = -tag[None, None, :, None].to(kp.dtype)
+    kv_fill(kv, kp, vp)
     d_out = torch.zeros(tr.STEP_OUT_INTS, dtype=torch.int32, device="cuda")
     h = ctx.accept_and_update(kv, torch.from_numpy(S.astype(np.int32)).cuda(),
                               torch.from_numpy(topk.astype(np.int32)).cuda(), d_out, sync=True)
     assert int(kv.d_len.item()) == h.kv_len == kv.c.len_bound
-    return h, ctx.matrix_store(), kv.k.cpu().numpy(), kv.v.cpu().numpy(), ctx
+    kc, vc = kv_plain_views(kv)
+    return h, ctx.matrix_store(), kc.float().cpu().numpy(), vc.float().cpu().numpy(), ctx
 
 
 def test_chain_accept_example_on_gpu(golden):
@@ -152,9 +156,12 @@ def test_chain_accept_example_on_gpu(golden):
     assert h.n_accepted == int(g["expect_matched"][0][0]) and h.next_root == 5
 
 
-@pytest.mark.parametrize("name", ["tree80", "tree81", "tree15", "wide128", "single"])
-def test_accept_update_compact_matches_oracle(name):
+@pytest.mark.parametrize("name,kvmode", [("tree80", "plain"), ("tree81", "plain"), ("tree15", "plain"),
+                                         ("wide128", "plain"), ("single", "plain"), ("tree80", "tiled"),
+                                         ("wide128", "tiled")])
+def test_accept_update_compact_matches_oracle(name, kvmode):
     require_gpu()
+    kw = dict(hd=128, dtype="bf16") if kvmode == "tiled" else {}
     t = synth.TEMPLATES[name]()
     tree = O.make_tree(t.parent, t.rank, K)
     rng = np.random.default_rng(23)
@@ -171,7 +178,7 @@ def test_accept_update_compact_matches_oracle(name):
             for i in range(1, len(tree.paths[n])):
                 topk[tree.paths[n][i - 1], 0] = S[tree.paths[n][i]]
         say("accept", name, "trial", trial)
-        h, M, kc, vc, ctx = _run_accept(t, S, topk)
+        h, M, kc, vc, ctx = _run_accept(t, S, topk, **kw)
         acc = O.accept(S, topk[:, 0], tree)
         assert h.n_accepted == acc.n_accepted and h.winner == acc.winner
         assert list(h.path[:h.n_emitted]) == acc.path
@@ -183,8 +190,8 @@ def test_accept_update_compact_matches_oracle(name):
         # compaction: cache position L+i holds the row the forward wrote for node path[i]
         for i, node in enumerate(acc.path):
             assert (kc[:, :, L + i, :] == 100.0 + node).all()
-            assert (vc[:, :, :, L + i] == -(100.0 + node)).all()
-        assert (kc[:, :, :L, :] == 0).all() and (vc[:, :, :, :L] == 0).all()
+            assert (vc[:, :, L + i, :] == -(100.0 + node)).all()
+        assert (kc[:, :, :L, :] == 0).all() and (vc[:, :, :L, :] == 0).all()
         depths.add(acc.n_accepted)
         ctx.close()
     if name != "single":
