@@ -116,7 +116,7 @@ tr_status tr_create(int32_t V, int32_t k, const tr_tree_template *t, tr_ctx **ou
   const int n = t->n_nodes, cn = TR_MAX_NODES;
   const size_t ints = 3 * (size_t)(n + cn) * sizeof(int32_t);
   const size_t ancs = 2 * (size_t)(n + cn) * sizeof(uint64_t);
-  const size_t blob = ints + ancs + sizeof(int32_t) * 64;
+  const size_t blob = ints + ancs + sizeof(int32_t) * 64 + topk_scratch_bytes();
   unsigned char *h = new (std::nothrow) unsigned char[blob];
   if (h == nullptr) {
     delete c;
@@ -158,6 +158,7 @@ tr_status tr_create(int32_t V, int32_t k, const tr_tree_template *t, tr_ctx **ou
   c->tree = TreeDev{n, t->n_layers, di, di + n, di + 2 * n, da};
   c->chain = TreeDev{cn, cn, di + 3 * n, di + 3 * n + cn, di + 3 * n + 2 * cn, da + 2 * n};
   c->d_step_L = reinterpret_cast<int32_t *>(d + ints + ancs);
+  c->d_topk_cand = d + ints + ancs + sizeof(int32_t) * 64;
   *out = c;
   return TR_OK;
 }
@@ -216,7 +217,7 @@ tr_status tr_verify_forward(tr_ctx *c, const tr_model *m, tr_kv *kv, const int32
   hipStream_t st = as_stream(stream);
   if (run_forward(*m, *kv, c->tree, n, d_S, logits, ws, &c->prof, st) != hipSuccess) return TR_EHIP;
   ProfScope ps(&c->prof, PC_TOPK, st);
-  if (launch_topk(logits, TR_F32, n, m->vocab, c->k, d_topk, st) != hipSuccess) return TR_EHIP;
+  if (launch_topk(logits, TR_F32, n, m->vocab, c->k, d_topk, c->d_topk_cand, st) != hipSuccess) return TR_EHIP;
   return TR_OK;
 }
 
@@ -261,7 +262,7 @@ tr_status tr_prefill(tr_ctx *c, const tr_model *m, tr_kv *kv, const int32_t *d_t
 tr_status tr_op_topk(tr_ctx *c, const void *d_logits, int32_t dtype, int32_t n_rows, int32_t *d_topk, void *stream) {
   if (c == nullptr || d_logits == nullptr || d_topk == nullptr || n_rows < 0) return TR_EINVAL;
   if (dtype != TR_F32 && dtype != TR_BF16) return TR_EINVAL;
-  return launch_topk(d_logits, dtype, n_rows, c->V, c->k, d_topk, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;
+  return launch_topk(d_logits, dtype, n_rows, c->V, c->k, d_topk, c->d_topk_cand, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;
 }
 
 tr_status tr_op_matrix_update(tr_ctx *c, const int32_t *d_S, const int32_t *d_topk, void *stream) {

@@ -6,6 +6,8 @@
 // Arithmetic contract of the bf16 path (both generic and MFMA kernels): the residual stream, the
 // softmax statistics, all accumulators and the logits are float32; operands of every contraction
 // (normalised activations, rotated Q/K, V, attention output, SwiGLU output) are rounded to bf16.
+// In the packed path the RMS scale is applied after the contraction (it is a per-row scalar), i.e.
+// the rounded operand is x * gain instead of x * gain * scale.
 #include "tr_internal.h"
 #include "tr_kernels.h"
 
@@ -21,7 +23,7 @@ Workspace plan_workspace(const tr_model &m) {
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
   w.x = take((size_t)NP * m.d_model * 4);
   w.xn = take((size_t)NP * m.d_model * esz);
-  w.qkv = take((size_t)NP * (hq + 2 * hk) * 4);
+  w.qkv = take((size_t)GEMM_MAX_SPLITS * NP * (hq + 2 * hk) * 4);
   w.q = take((size_t)NP * hq * esz);
   w.attn = take((size_t)NP * hq * esz);
   w.gu = take((size_t)NP * 2 * m.d_ffn * 4);
@@ -31,6 +33,7 @@ Workspace plan_workspace(const tr_model &m) {
   w.part_ml = take((size_t)ATTN_MAX_SPLITS * NP * m.n_heads * 2 * 4);
   w.part_acc = take((size_t)ATTN_MAX_SPLITS * NP * m.n_heads * m.head_dim * 4);
   w.ypart = take((size_t)GEMM_MAX_SPLITS * NP * m.d_model * 4);
+  w.ssq = take((size_t)NP * ((m.d_model + 1023) / 1024) * 4);
   w.total = off;
   return w;
 }
@@ -146,8 +149,9 @@ __global__ __launch_bounds__(256) void k_swiglu(const float *__restrict__ gu, in
 // Rotated q -> q[n, h, :]; rotated k -> K[layer][h][L+n][:]; v -> V[layer][h][:][L+n].
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(128) void k_rope_kv(const float *__restrict__ qkv, const float *__restrict__ rope,
-                                                 int32_t H, int32_t Hkv, int32_t hd, int32_t cap,
+__global__ __launch_bounds__(128) void k_rope_kv(const float *__restrict__ qkv, int32_t n_part, size_t part_stride,
+                                                 const float *__restrict__ rope, int32_t H, int32_t Hkv, int32_t hd,
+                                                 int32_t cap,
                                                  const int32_t *__restrict__ d_len, T *__restrict__ q,
                                                  T *__restrict__ Kl, T *__restrict__ Vl, int32_t tiled) {
   const int n = blockIdx.x, hh = blockIdx.y;
@@ -155,10 +159,16 @@ __global__ __launch_bounds__(128) void k_rope_kv(const float *__restrict__ qkv, 
   const int width = (H + 2 * Hkv) * hd;
   const float *src = qkv + (size_t)n * width + (size_t)hh * hd;
   const int pos = *d_len + n;
+  // the projection may arrive as n_part K-split partial sums, added here in split order
+  auto val = [&](int i) {
+    float v = src[i];
+    for (int s = 1; s < n_part; ++s) v += src[(size_t)s * part_stride + i];
+    return v;
+  };
   if (hh < H + Hkv) {
     for (int i = threadIdx.x; i < half; i += blockDim.x) {
       const float c = rope[(size_t)n * hd + i], s = rope[(size_t)n * hd + half + i];
-      const float a = src[i], b = src[i + half];
+      const float a = val(i), b = val(i + half);
       const T ra = from_f32<T>(a * c - b * s), rb = from_f32<T>(b * c + a * s);
       if (hh < H) {
         T *dst = q + ((size_t)n * H + hh) * hd;
@@ -176,10 +186,10 @@ __global__ __launch_bounds__(128) void k_rope_kv(const float *__restrict__ qkv, 
     }
   } else if (tiled) {
     T *dst = Vl + (size_t)(hh - H - Hkv) * hd * cap;
-    for (int i = threadIdx.x; i < hd; i += blockDim.x) dst[kv_v_index(pos, i)] = from_f32<T>(src[i]);
+    for (int i = threadIdx.x; i < hd; i += blockDim.x) dst[kv_v_index(pos, i)] = from_f32<T>(val(i));
   } else {
     T *dst = Vl + (size_t)(hh - H - Hkv) * hd * cap + pos;
-    for (int i = threadIdx.x; i < hd; i += blockDim.x) dst[(size_t)i * cap] = from_f32<T>(src[i]);
+    for (int i = threadIdx.x; i < hd; i += blockDim.x) dst[(size_t)i * cap] = from_f32<T>(val(i));
   }
 }
 
@@ -324,8 +334,8 @@ static hipError_t forward_generic(const tr_model &m, const tr_kv &kv, const Tree
     }
     {
       ProfScope ps(prof, PC_ROPE, st);
-      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, rope, H, Hkv, hd, kv.capacity,
-                         kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, kv.layout);
+      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, 1, (size_t)0, rope, H, Hkv, hd,
+                         kv.capacity, kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, kv.layout);
       TR_TRY(hipGetLastError());
     }
     {
@@ -371,49 +381,55 @@ static hipError_t forward_generic(const tr_model &m, const tr_kv &kv, const Tree
 // fragment order, projection outputs that feed the residual stream kept as per-split partial sums
 // which the next normalisation kernel folds into x in a fixed order.
 // ---------------------------------------------------------------------------------------------
-// x[row,:] += sum_s part[s][row,:]  (n_part may be 0), then xn = bf16(rmsnorm(x) * g) in fragment order.
-// Rows n..16*row_tiles-1 are written as zeros.
-__global__ __launch_bounds__(256) void k_addnorm_frag(float *__restrict__ x, const float *__restrict__ part,
-                                                      int32_t n_part, size_t part_stride, const bf16_t *__restrict__ g,
-                                                      int32_t n, int32_t d, float eps, int32_t row_tiles,
-                                                      bf16_t *__restrict__ xn_frag) {
-  __shared__ float red[4];
-  const int row = blockIdx.x;
-  const bool live = row < n;
-  float *xr = x + (size_t)row * d;
+// Residual update and normalisation input, block (row, chunk of 1024 columns), 128 threads x 8 columns:
+//   x[row, c] += sum_s part[s][row, c]        (n_part may be 0)
+//   xg_frag    = bf16(x * g)                   fragment order; rows n..16*row_tiles-1 are zeros
+//   ssq[row, chunk] = sum over the chunk of x^2
+// The RMS scale 1/sqrt(mean(x^2) + eps) is a per-row scalar, so the GEMM that consumes xg_frag applies
+// it to its output rows (gemm row_ssq arguments) instead of this kernel needing a whole-row reduction.
+constexpr int NORM_CHUNK = 1024;
+static_assert(NORM_CHUNK == 128 * 8, "one block iteration covers 128 threads x 8 columns");
+__global__ __launch_bounds__(128) void k_add_frag(float *__restrict__ x, const float *__restrict__ part,
+                                                  int32_t n_part, size_t part_stride, const bf16_t *__restrict__ g,
+                                                  int32_t n, int32_t d, int32_t row_tiles,
+                                                  bf16_t *__restrict__ xg_frag, float *__restrict__ ssq,
+                                                  int32_t n_chunks) {
+  __shared__ float red[2];
+  const int row = blockIdx.x, chunk = blockIdx.y;
+  const int j = chunk * NORM_CHUNK + threadIdx.x * 8;
+  const bool live = row < n && j < d;
   float ss = 0.f;
+  uint4 pk = uint4{0u, 0u, 0u, 0u};
   if (live) {
-    for (int j = threadIdx.x * 4; j < d; j += 1024) {
-      float4 v = *reinterpret_cast<const float4 *>(xr + j);
-      for (int s = 0; s < n_part; ++s) {
-        const float4 p = *reinterpret_cast<const float4 *>(part + (size_t)s * part_stride + (size_t)row * d + j);
-        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-      }
-      if (n_part > 0) *reinterpret_cast<float4 *>(xr + j) = v;
-      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    float *xr = x + (size_t)row * d + j;
+    float4 a = *reinterpret_cast<const float4 *>(xr), b = *reinterpret_cast<const float4 *>(xr + 4);
+    for (int s = 0; s < n_part; ++s) {
+      const float *pr = part + (size_t)s * part_stride + (size_t)row * d + j;
+      const float4 pa = *reinterpret_cast<const float4 *>(pr), pb = *reinterpret_cast<const float4 *>(pr + 4);
+      a.x += pa.x; a.y += pa.y; a.z += pa.z; a.w += pa.w;
+      b.x += pb.x; b.y += pb.y; b.z += pb.z; b.w += pb.w;
     }
+    if (n_part > 0) {
+      *reinterpret_cast<float4 *>(xr) = a;
+      *reinterpret_cast<float4 *>(xr + 4) = b;
+    }
+    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    const uint4 gv = *reinterpret_cast<const uint4 *>(g + j);
+    const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float g0 = bf16_to_f32((bf16_t)(gw[e] & 0xFFFFu)), g1 = bf16_to_f32((bf16_t)(gw[e] >> 16));
+      o[e] = (uint32_t)f32_to_bf16(v[2 * e] * g0) | ((uint32_t)f32_to_bf16(v[2 * e + 1] * g1) << 16);
+      ss += v[2 * e] * v[2 * e] + v[2 * e + 1] * v[2 * e + 1];
+    }
+    pk = uint4{o[0], o[1], o[2], o[3]};
   }
+  if (j < d) *reinterpret_cast<uint4 *>(xg_frag + act_frag_index(row, j, row_tiles)) = pk;
   for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
-  const float r = 1.0f / sqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)d + eps);
-  for (int j = threadIdx.x * 8; j < d; j += 2048) {
-    uint4 pk = uint4{0u, 0u, 0u, 0u};
-    if (live) {
-      const float4 a = *reinterpret_cast<const float4 *>(xr + j), b = *reinterpret_cast<const float4 *>(xr + j + 4);
-      const uint4 gv = *reinterpret_cast<const uint4 *>(g + j);
-      const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-      const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w};
-      uint32_t o[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float g0 = bf16_to_f32((bf16_t)(gw[e] & 0xFFFFu)), g1 = bf16_to_f32((bf16_t)(gw[e] >> 16));
-        o[e] = (uint32_t)f32_to_bf16(v[2 * e] * r * g0) | ((uint32_t)f32_to_bf16(v[2 * e + 1] * r * g1) << 16);
-      }
-      pk = uint4{o[0], o[1], o[2], o[3]};
-    }
-    *reinterpret_cast<uint4 *>(xn_frag + act_frag_index(row, j, row_tiles)) = pk;
-  }
+  if (threadIdx.x == 0 && row < n) ssq[(size_t)row * n_chunks + chunk] = red[0] + red[1];
 }
 
 // row-major bf16 [n, K] -> fragment order (standalone linear op only)
@@ -436,15 +452,9 @@ __global__ __launch_bounds__(256) void k_sum_parts(const float *__restrict__ par
   y[i] = v;
 }
 
-static int choose_splits(int out_tiles) {
-  int s = 1;
-  while (s < GEMM_MAX_SPLITS && (out_tiles / 2) * s < 256) s *= 2;
-  return s;
-}
-
 static bool packed_supported(const tr_model &m) {
   const int hq = m.n_heads * m.head_dim, hk = m.n_kv_heads * m.head_dim;
-  return m.dtype == TR_BF16 && m.layout == TR_PACKED && m.d_model % 32 == 0 && m.d_ffn % 32 == 0 && hq % 32 == 0 &&
+  return m.dtype == TR_BF16 && m.layout == TR_PACKED && m.d_model % 32 == 0 && m.d_model <= 8 * NORM_CHUNK && m.d_ffn % 32 == 0 && hq % 32 == 0 &&
          hk % 32 == 0 && m.vocab % 32 == 0;
 }
 
@@ -465,7 +475,9 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
   float *ypart = (float *)(ws + w.ypart);
   const size_t ystride = (size_t)NP * d;
   const size_t lsz = (size_t)Hkv * kv.capacity * hd;
-  const int s_d = choose_splits(d / 16); // K-splits of the two projections that feed the residual stream
+  const size_t qstride = (size_t)NP * wq;
+  float *ssq = (float *)(ws + w.ssq);
+  const int nch = (d + NORM_CHUNK - 1) / NORM_CHUNK;
 
   {
     ProfScope ps(prof, PC_EMBED, st);
@@ -474,12 +486,13 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
     TR_TRY(hipGetLastError());
   }
   int pending = 0; // partial sums waiting in ypart
+  int qkv_parts = 1;
   for (int l = 0; l < m.n_layers; ++l) {
     const tr_layer &lw = m.layers[l];
     {
       ProfScope ps(prof, PC_NORM, st);
-      hipLaunchKernelGGL(k_addnorm_frag, dim3(NT * 16), dim3(256), 0, st, x, ypart, pending, ystride,
-                         (const T *)lw.attn_norm, n, d, m.rms_eps, NT, xn);
+      hipLaunchKernelGGL(k_add_frag, dim3(NT * 16, nch), dim3(128), 0, st, x, ypart, pending, ystride,
+                         (const T *)lw.attn_norm, n, d, NT, xn, ssq, nch);
       TR_TRY(hipGetLastError());
     }
     {
@@ -489,13 +502,17 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
       g.seg[0] = GemmSeg{(const T *)lw.wq, hq / 16};
       g.seg[1] = GemmSeg{(const T *)lw.wk, hk / 16};
       g.seg[2] = GemmSeg{(const T *)lw.wv, hk / 16};
-      g.n_seg = 3; g.y = qkv; g.ldy = wq; g.splits = 1; g.split_stride = 0; g.mode = GEMM_STORE;
+      g.n_seg = 3; g.y = qkv; g.ldy = wq; g.split_stride = qstride; g.mode = GEMM_STORE;
+      g.row_ssq = ssq; g.n_ssq = nch; g.norm_dim = d; g.eps = m.rms_eps;
+      gemm_plan(g, GEMM_MAX_SPLITS);
+      qkv_parts = g.splits;
       TR_TRY(launch_gemm_mfma(g, st));
     }
     {
       ProfScope ps(prof, PC_ROPE, st);
-      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, rope, H, Hkv, hd, kv.capacity,
-                         kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, kv.layout);
+      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, qkv_parts, qstride, rope, H, Hkv,
+                         hd, kv.capacity, kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz,
+                         kv.layout);
       TR_TRY(hipGetLastError());
     }
     {
@@ -508,13 +525,15 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
       GemmArgs g{};
       g.a_frag = attn; g.n = n; g.K = hq;
       g.seg[0] = GemmSeg{(const T *)lw.wo, d / 16};
-      g.n_seg = 1; g.y = ypart; g.ldy = d; g.splits = s_d; g.split_stride = ystride; g.mode = GEMM_STORE;
+      g.n_seg = 1; g.y = ypart; g.ldy = d; g.split_stride = ystride; g.mode = GEMM_STORE;
+      gemm_plan(g, GEMM_MAX_SPLITS);
+      pending = g.splits;
       TR_TRY(launch_gemm_mfma(g, st));
     }
     {
       ProfScope ps(prof, PC_NORM, st);
-      hipLaunchKernelGGL(k_addnorm_frag, dim3(NT * 16), dim3(256), 0, st, x, ypart, s_d, ystride,
-                         (const T *)lw.ffn_norm, n, d, m.rms_eps, NT, xn);
+      hipLaunchKernelGGL(k_add_frag, dim3(NT * 16, nch), dim3(128), 0, st, x, ypart, pending, ystride,
+                         (const T *)lw.ffn_norm, n, d, NT, xn, ssq, nch);
       TR_TRY(hipGetLastError());
     }
     {
@@ -522,7 +541,9 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
       GemmArgs g{};
       g.a_frag = xn; g.n = n; g.K = d;
       g.seg[0] = GemmSeg{(const T *)lw.w_gate, F / 16};
-      g.n_seg = 1; g.w2 = (const T *)lw.w_up; g.splits = 1; g.h_frag = hbuf; g.mode = GEMM_SWIGLU;
+      g.n_seg = 1; g.w2 = (const T *)lw.w_up; g.h_frag = hbuf; g.mode = GEMM_SWIGLU;
+      g.row_ssq = ssq; g.n_ssq = nch; g.norm_dim = d; g.eps = m.rms_eps;
+      gemm_plan(g, 1);
       TR_TRY(launch_gemm_mfma(g, st));
     }
     {
@@ -530,23 +551,26 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
       GemmArgs g{};
       g.a_frag = hbuf; g.n = n; g.K = F;
       g.seg[0] = GemmSeg{(const T *)lw.w_down, d / 16};
-      g.n_seg = 1; g.y = ypart; g.ldy = d; g.splits = s_d; g.split_stride = ystride; g.mode = GEMM_STORE;
+      g.n_seg = 1; g.y = ypart; g.ldy = d; g.split_stride = ystride; g.mode = GEMM_STORE;
+      gemm_plan(g, GEMM_MAX_SPLITS);
+      pending = g.splits;
       TR_TRY(launch_gemm_mfma(g, st));
     }
-    pending = s_d;
   }
   if (logits_out != nullptr) {
     {
       ProfScope ps(prof, PC_NORM, st);
-      hipLaunchKernelGGL(k_addnorm_frag, dim3(NT * 16), dim3(256), 0, st, x, ypart, pending, ystride,
-                         (const T *)m.final_norm, n, d, m.rms_eps, NT, xn);
+      hipLaunchKernelGGL(k_add_frag, dim3(NT * 16, nch), dim3(128), 0, st, x, ypart, pending, ystride,
+                         (const T *)m.final_norm, n, d, NT, xn, ssq, nch);
       TR_TRY(hipGetLastError());
     }
     ProfScope ps(prof, PC_LMHEAD, st);
     GemmArgs g{};
     g.a_frag = xn; g.n = n; g.K = d;
     g.seg[0] = GemmSeg{(const T *)m.lm_head, m.vocab / 16};
-    g.n_seg = 1; g.y = logits_out; g.ldy = m.vocab; g.splits = 1; g.split_stride = 0; g.mode = GEMM_STORE;
+    g.n_seg = 1; g.y = logits_out; g.ldy = m.vocab; g.split_stride = 0; g.mode = GEMM_STORE;
+    g.row_ssq = ssq; g.n_ssq = nch; g.norm_dim = d; g.eps = m.rms_eps;
+    gemm_plan(g, 1);
     TR_TRY(launch_gemm_mfma(g, st));
   }
   return hipSuccess;
@@ -590,8 +614,10 @@ hipError_t run_linear(const void *x, const void *w, int32_t dtype, int32_t layou
     GemmArgs g{};
     g.a_frag = frag; g.n = n; g.K = in_f;
     g.seg[0] = GemmSeg{(const bf16_t *)w, out_f / 16};
-    g.n_seg = 1; g.y = splits > 1 ? part : y; g.ldy = out_f; g.splits = splits;
+    g.n_seg = 1; g.y = splits > 1 ? part : y; g.ldy = out_f;
     g.split_stride = (size_t)n * out_f; g.mode = GEMM_STORE;
+    gemm_plan(g, splits);
+    g.splits = splits; // the caller's split count is used as given
     TR_TRY(launch_gemm_mfma(g, st));
     if (splits > 1) {
       const size_t count = (size_t)n * out_f;

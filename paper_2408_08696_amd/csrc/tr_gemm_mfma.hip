@@ -13,10 +13,15 @@
 // With A = weight tile and B = activation tile, lane l ends with outputs o0 + 4*(l/16) .. +3 of row
 // 16*nt + l%16.
 //
-// Mapping.  One workgroup owns OT consecutive out-tiles (16*OT output features) and one of `splits`
+// Mapping.  One workgroup owns NW consecutive out-tiles (16*NW output features) and one of `splits`
 // K-ranges; its 8 wavefronts take interleaved k-tiles of that range, keep PF k-steps of loads in flight
 // in registers, and reduce through LDS in a fixed binary tree at the end.  splits > 1 writes one partial
 // result per split (summed in a fixed order by the consumer), so results are run-to-run deterministic.
+//
+// Why NW is large.  Every workgroup reads the whole activation block of its K-range from L2 (16*NT rows),
+// so L2 carries (1 + 16*NT / (16*NW)) bytes per weight byte; measured L2->CU throughput on MI355X is only
+// about twice the HBM rate, so the kernel stays HBM-bound only while NW >= NT.  launch_gemm_mfma picks
+// (NW, splits) to get close to one workgroup per compute unit with NW as large as registers allow.
 #include "tr_kernels.h"
 
 namespace tr {
@@ -26,7 +31,12 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int GEMM_WAVES = 8;
-constexpr int GEMM_PF = 4; // k-steps of loads in flight per wave
+// k-steps of loads in flight per wave, bounded by the register file: accumulators take 4*NW*NT VGPRs,
+// every stage 4*(NW+NT); 256 VGPRs per wave at two waves per SIMD, about 208 of them usable here
+__host__ __device__ constexpr int gemm_pf(int nw, int nt) {
+  const int pf = (208 - 4 * nw * nt) / (4 * (nw + nt));
+  return pf < 1 ? 1 : (pf > 4 ? 4 : pf);
+}
 
 __device__ inline f32x4 mfma16(const u32x4 &a, const u32x4 &b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -60,31 +70,30 @@ hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t
 // ---------------------------------------------------------------------------------------------
 // the GEMM
 // ---------------------------------------------------------------------------------------------
-template <int NT, int OT, int MODE>
+template <int NT, int NW, int MODE>
 __global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(GemmArgs g) {
-  // SWIGLU: OT must be 1; "tile 0" is the gate matrix, "tile 1" the up matrix, same out-tile index
-  constexpr int NW = MODE == GEMM_SWIGLU ? 2 : OT;
+  // SWIGLU: NW = 2P; weight tiles 0..P-1 come from the gate matrix, P..2P-1 from the up matrix
+  constexpr int P = MODE == GEMM_SWIGLU ? NW / 2 : NW; // distinct out-tiles per workgroup
+  constexpr int PF = gemm_pf(NW, NT);
   extern __shared__ float red[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int KT = g.K / 32;
 
-  // which segment (weight matrix) and out-tile does this workgroup own
-  int tile0 = blockIdx.x * OT; // global out-tile index across the concatenated segments
+  // out-tiles owned by this workgroup, numbered across the concatenated segments (weight matrices);
+  // each tile looks up its own segment, so a workgroup may straddle two matrices
+  const int tile0 = blockIdx.x * P;
+  const int n_valid = g.total_tiles - tile0 < P ? g.total_tiles - tile0 : P;
   const u32x4 *wbase[NW];
-  {
-    int t = tile0, sidx = 0;
+#pragma unroll
+  for (int u = 0; u < P; ++u) {
+    int t = tile0 + (u < n_valid ? u : 0); // tiles past the end re-read a valid tile, never stored
+    int sidx = 0;
     while (sidx + 1 < g.n_seg && t >= g.seg[sidx].out_tiles) {
       t -= g.seg[sidx].out_tiles;
       ++sidx;
     }
-    const u32x4 *w = reinterpret_cast<const u32x4 *>(g.seg[sidx].w) + (size_t)t * KT * 64 + lane;
-    if (MODE == GEMM_SWIGLU) {
-      wbase[0] = w;
-      wbase[NW - 1] = reinterpret_cast<const u32x4 *>(g.w2) + (size_t)t * KT * 64 + lane;
-    } else {
-#pragma unroll
-      for (int u = 0; u < NW; ++u) wbase[u] = w + (size_t)u * KT * 64;
-    }
+    wbase[u] = reinterpret_cast<const u32x4 *>(g.seg[sidx].w) + (size_t)t * KT * 64 + lane;
+    if (MODE == GEMM_SWIGLU) wbase[P + u] = reinterpret_cast<const u32x4 *>(g.w2) + (size_t)t * KT * 64 + lane;
   }
   const u32x4 *abase = reinterpret_cast<const u32x4 *>(g.a_frag) + lane;
 
@@ -102,7 +111,19 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(GemmArgs g) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  u32x4 wq[GEMM_PF][NW], aq[GEMM_PF][NT];
+  // optional per-row RMS scale for the epilogue (wave 0 only).  Lane group g fetches chunks g and g+4 of
+  // its row's sums of squares now, with no dependent arithmetic, so the loads retire under the main
+  // loop; the epilogue adds the groups with two shuffles (n_ssq <= 8).
+  float row_ss[NT][2];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int row = 16 * t + (lane & 15), c0 = lane >> 4;
+    const bool on = wave == 0 && g.row_ssq != nullptr && row < g.n;
+    row_ss[t][0] = on && c0 < g.n_ssq ? g.row_ssq[(size_t)row * g.n_ssq + c0] : 0.f;
+    row_ss[t][1] = on && c0 + 4 < g.n_ssq ? g.row_ssq[(size_t)row * g.n_ssq + c0 + 4] : 0.f;
+  }
+
+  u32x4 wq[PF][NW], aq[PF][NT];
   auto issue = [&](int stage, int step) {
     const size_t kt = (size_t)(first + step * GEMM_WAVES);
 #pragma unroll
@@ -111,17 +132,17 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(GemmArgs g) {
     for (int t = 0; t < NT; ++t) aq[stage][t] = abase[(kt * NT + t) * 64];
   };
 #pragma unroll
-  for (int j = 0; j < GEMM_PF; ++j)
+  for (int j = 0; j < PF; ++j)
     if (j < nsteps) issue(j, j);
-  for (int base = 0; base < nsteps; base += GEMM_PF) {
+  for (int base = 0; base < nsteps; base += PF) {
 #pragma unroll
-    for (int j = 0; j < GEMM_PF; ++j) {
+    for (int j = 0; j < PF; ++j) {
       if (base + j < nsteps) {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
           for (int u = 0; u < NW; ++u) acc[u][t] = mfma16(wq[j][u], aq[j][t], acc[u][t]);
-        if (base + j + GEMM_PF < nsteps) issue(j, base + j + GEMM_PF);
+        if (base + j + PF < nsteps) issue(j, base + j + PF);
       }
     }
   }
@@ -156,27 +177,42 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(GemmArgs g) {
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int row = 16 * t + r;
+    if (g.row_ssq != nullptr) {
+      float ss = row_ss[t][0] + row_ss[t][1];
+      ss += __shfl_xor(ss, 16);
+      ss += __shfl_xor(ss, 32);
+      const float sc = 1.0f / sqrtf(ss / (float)g.norm_dim + g.eps);
+#pragma unroll
+      for (int u = 0; u < NW; ++u) {
+        acc[u][t][0] *= sc; acc[u][t][1] *= sc; acc[u][t][2] *= sc; acc[u][t][3] *= sc;
+      }
+    }
     if (MODE == GEMM_STORE) {
       if (row >= g.n) continue;
       float *yb = g.y + (size_t)split * g.split_stride + (size_t)row * g.ldy;
 #pragma unroll
-      for (int u = 0; u < NW; ++u) {
+      for (int u = 0; u < P; ++u) {
+        if (u >= n_valid) continue;
         const int o = (tile0 + u) * 16 + 4 * gq;
         *reinterpret_cast<float4 *>(yb + o) = float4{acc[u][t][0], acc[u][t][1], acc[u][t][2], acc[u][t][3]};
       }
     } else {
       // h[row, o .. o+3] = bf16(silu(gate) * up), written in fragment order over (k = o, NT row tiles);
       // rows past n are written as zeros so the consumer's operand tiles are fully defined
-      const f32x4 gt = acc[0][t], up = acc[NW - 1][t];
       const bool live = row < g.n;
-      ushort4 hv;
-      hv.x = live ? f32_to_bf16(gt[0] / (1.0f + __expf(-gt[0])) * up[0]) : (bf16_t)0;
-      hv.y = live ? f32_to_bf16(gt[1] / (1.0f + __expf(-gt[1])) * up[1]) : (bf16_t)0;
-      hv.z = live ? f32_to_bf16(gt[2] / (1.0f + __expf(-gt[2])) * up[2]) : (bf16_t)0;
-      hv.w = live ? f32_to_bf16(gt[3] / (1.0f + __expf(-gt[3])) * up[3]) : (bf16_t)0;
-      const int o = tile0 * 16 + 4 * gq;                 // k index of the consumer
-      const size_t slot = ((size_t)(o >> 5) * NT + t) * 64 + r + 16 * ((o & 31) >> 3);
-      *reinterpret_cast<ushort4 *>(g.h_frag + slot * 8 + (o & 7)) = hv;
+#pragma unroll
+      for (int u = 0; u < P; ++u) {
+        if (u >= n_valid) continue;
+        const f32x4 gt = acc[u][t], up = acc[MODE == GEMM_SWIGLU ? P + u : u][t];
+        ushort4 hv;
+        hv.x = live ? f32_to_bf16(gt[0] / (1.0f + __expf(-gt[0])) * up[0]) : (bf16_t)0;
+        hv.y = live ? f32_to_bf16(gt[1] / (1.0f + __expf(-gt[1])) * up[1]) : (bf16_t)0;
+        hv.z = live ? f32_to_bf16(gt[2] / (1.0f + __expf(-gt[2])) * up[2]) : (bf16_t)0;
+        hv.w = live ? f32_to_bf16(gt[3] / (1.0f + __expf(-gt[3])) * up[3]) : (bf16_t)0;
+        const int o = (tile0 + u) * 16 + 4 * gq; // k index of the consumer
+        const size_t slot = ((size_t)(o >> 5) * NT + t) * 64 + r + 16 * ((o & 31) >> 3);
+        *reinterpret_cast<ushort4 *>(g.h_frag + slot * 8 + (o & 7)) = hv;
+      }
     }
   }
 }
@@ -185,40 +221,84 @@ bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O) {
   return n >= 1 && n <= TR_MAX_NODES && K % 32 == 0 && O % 32 == 0;
 }
 
-template <int NT, int OT, int MODE>
-static hipError_t launch_k(const GemmArgs &g, int total_tiles, hipStream_t st) {
-  constexpr int NW = MODE == GEMM_SWIGLU ? 2 : OT;
+// Pick (P out-tiles per workgroup, K-splits).  Cost model in KiB moved through L2 per workgroup, times
+// the number of rounds 256 compute units need: per k-tile a workgroup reads `wt` KiB of weights and NT
+// KiB of activations; with splits > 1 every workgroup also writes (and the consumer re-reads) wt*NT KiB.
+void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, const int32_t *seg_tiles, int32_t n_seg, bool swiglu,
+                 int32_t max_splits, int32_t *out_p, int32_t *out_splits) {
+  const int NT = (n + 15) / 16, KT = K / 32;
+  static const int cand[] = {1, 2, 3, 4, 6};
+  double best = 1e30;
+  int bp = 1, bs = 1;
+  for (int ci = 0; ci < 5; ++ci) {
+    const int p = cand[ci];
+    const int wt = swiglu ? 2 * p : p;
+    if (wt > 6 || wt * NT > 32) continue; // accumulators must fit the register file
+    for (int s = 1; s <= max_splits; s *= 2) {
+      if (KT / s < GEMM_WAVES) break;
+      const int wgs = ((total_tiles + p - 1) / p) * s;
+      const int rounds = (wgs + 255) / 256;
+      const double per_wg = (double)((KT + s - 1) / s) * (wt + NT) + (s > 1 ? 2.0 * wt * NT : 0.0) + 40.0;
+      const double cost = rounds * per_wg;
+      if (cost < best) {
+        best = cost;
+        bp = p;
+        bs = s;
+      }
+    }
+  }
+  *out_p = bp;
+  *out_splits = bs;
+}
+
+template <int NT, int NW, int MODE>
+static hipError_t launch_k(const GemmArgs &g, int p, hipStream_t st) {
   const size_t smem = (size_t)(GEMM_WAVES / 2) * NW * NT * 64 * 16;
-  hipLaunchKernelGGL((k_gemm_mfma<NT, OT, MODE>), dim3(total_tiles / OT, g.splits), dim3(GEMM_WAVES * 64), smem, st, g);
+  if (smem > 65536) {
+    static bool once = [] {
+      return hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mfma<NT, NW, MODE>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess;
+    }();
+    if (!once) return hipErrorInvalidValue;
+  }
+  hipLaunchKernelGGL((k_gemm_mfma<NT, NW, MODE>), dim3((g.total_tiles + p - 1) / p, g.splits), dim3(GEMM_WAVES * 64),
+                     smem, st, g);
   return hipGetLastError();
 }
 
 template <int NT>
-static hipError_t launch_nt(const GemmArgs &g, int total_tiles, int ot, hipStream_t st) {
-  if (g.mode == GEMM_SWIGLU) return launch_k<NT, 1, GEMM_SWIGLU>(g, total_tiles, st);
-  if (ot == 2) return launch_k<NT, 2, GEMM_STORE>(g, total_tiles, st);
-  return launch_k<NT, 1, GEMM_STORE>(g, total_tiles, st);
+static hipError_t launch_nt(const GemmArgs &g, hipStream_t st) {
+  const int p = g.tiles_per_wg;
+  if (g.mode == GEMM_SWIGLU) {
+    if constexpr (NT <= 5) {
+      if (p == 3) return launch_k<NT, 6, GEMM_SWIGLU>(g, p, st);
+    }
+    if (p == 2) return launch_k<NT, 4, GEMM_SWIGLU>(g, p, st);
+    if (p == 1) return launch_k<NT, 2, GEMM_SWIGLU>(g, p, st);
+    return hipErrorInvalidValue;
+  }
+  if constexpr (NT <= 5) {
+    if (p == 6) return launch_k<NT, 6, GEMM_STORE>(g, p, st);
+  }
+  switch (p) {
+  case 1: return launch_k<NT, 1, GEMM_STORE>(g, p, st);
+  case 2: return launch_k<NT, 2, GEMM_STORE>(g, p, st);
+  case 3: return launch_k<NT, 3, GEMM_STORE>(g, p, st);
+  case 4: return launch_k<NT, 4, GEMM_STORE>(g, p, st);
+  }
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st) {
-  int total = 0;
-  bool even = true;
-  for (int i = 0; i < g.n_seg; ++i) {
-    total += g.seg[i].out_tiles;
-    even = even && (g.seg[i].out_tiles % 2 == 0);
-  }
-  // two out-tiles per workgroup halve the activation re-reads; keep one when that would leave
-  // fewer workgroups than compute units
-  const int ot = (g.mode != GEMM_SWIGLU && even && (total / 2) * g.splits >= 256) ? 2 : 1;
   switch ((g.n + 15) / 16) {
-  case 1: return launch_nt<1>(g, total, ot, st);
-  case 2: return launch_nt<2>(g, total, ot, st);
-  case 3: return launch_nt<3>(g, total, ot, st);
-  case 4: return launch_nt<4>(g, total, ot, st);
-  case 5: return launch_nt<5>(g, total, ot, st);
-  case 6: return launch_nt<6>(g, total, ot, st);
-  case 7: return launch_nt<7>(g, total, ot, st);
-  case 8: return launch_nt<8>(g, total, ot, st);
+  case 1: return launch_nt<1>(g, st);
+  case 2: return launch_nt<2>(g, st);
+  case 3: return launch_nt<3>(g, st);
+  case 4: return launch_nt<4>(g, st);
+  case 5: return launch_nt<5>(g, st);
+  case 6: return launch_nt<6>(g, st);
+  case 7: return launch_nt<7>(g, st);
+  case 8: return launch_nt<8>(g, st);
   }
   return hipErrorInvalidValue;
 }

@@ -92,15 +92,138 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const T *__restrict__ log
   }
 }
 
-hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k,
-                       int32_t *d_topk, hipStream_t st) {
+// Two-stage variant for k <= 8.  Stage 1, grid (row, segment): the row is cut into TOPK_SEGS segments;
+// every thread loads its (at most TOPK_PER_THREAD) elements of the segment at once, keeps them sorted in
+// registers, and k rounds of a workgroup-wide "best head of list" write the segment's k best candidates.
+// Stage 2, one wave per row: the TOPK_SEGS * k candidates are merged the same way.  Both stages use the
+// total order of k_topk, so ties resolve identically.
+constexpr int TOPK_SEGS = 8;
+constexpr int TOPK1_THREADS = 256;
+constexpr int TOPK_PER_THREAD = 8; // registers per thread; longer segments loop
+
+__device__ inline void insert8(Cand (&l)[8], const Cand &e) {
+  if (before(e, l[7])) {
+    bool placed = false;
+#pragma unroll
+    for (int p = 7; p >= 0; --p) {
+      if (!placed) {
+        if (p > 0 && before(e, l[p - 1])) {
+          l[p] = l[p - 1];
+        } else {
+          l[p] = e;
+          placed = true;
+        }
+      }
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(TOPK1_THREADS) void k_topk_stage1(const T *__restrict__ logits, int32_t V, int32_t k,
+                                                                Cand *__restrict__ cand) {
+  __shared__ Cand red[TOPK1_THREADS / 64];
+  const int rowi = blockIdx.x, seg = blockIdx.y, tid = threadIdx.x;
+  const T *row = logits + (size_t)rowi * V;
+  const int seg_len = (V + TOPK_SEGS - 1) / TOPK_SEGS;
+  const int lo = seg * seg_len;
+  const int hi = lo + seg_len < V ? lo + seg_len : V;
+  Cand l[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    l[p].v = -__builtin_inff();
+    l[p].i = 0x7FFFFFFF; // sentinel: after every real element
+  }
+  for (int j0 = lo + tid; j0 < hi; j0 += TOPK_PER_THREAD * TOPK1_THREADS) {
+    float batch[TOPK_PER_THREAD];
+#pragma unroll
+    for (int b = 0; b < TOPK_PER_THREAD; ++b) {
+      const int j = j0 + b * TOPK1_THREADS;
+      batch[b] = j < hi ? to_f32<T>(row[j]) : -__builtin_inff();
+    }
+#pragma unroll
+    for (int b = 0; b < TOPK_PER_THREAD; ++b) {
+      Cand e;
+      e.v = batch[b];
+      e.i = j0 + b * TOPK1_THREADS;
+      if (e.i < hi) insert8(l, e);
+    }
+  }
+  for (int p = 0; p < k; ++p) {
+    Cand best = l[0];
+    for (int off = 32; off > 0; off >>= 1) {
+      Cand o;
+      o.v = __shfl_xor(best.v, off);
+      o.i = __shfl_xor(best.i, off);
+      if (before(o, best)) best = o;
+    }
+    if ((tid & 63) == 0) red[tid >> 6] = best;
+    __syncthreads();
+    Cand b = red[0];
+#pragma unroll
+    for (int w = 1; w < TOPK1_THREADS / 64; ++w)
+      if (before(red[w], b)) b = red[w];
+    if (tid == 0) cand[((size_t)rowi * TOPK_SEGS + seg) * 8 + p] = b;
+    // the owner of the winning element pops it (real indices are unique; sentinels never need popping)
+    if (l[0].i == b.i && b.i != 0x7FFFFFFF) {
+#pragma unroll
+      for (int q = 0; q < 7; ++q) l[q] = l[q + 1];
+      l[7].v = -__builtin_inff();
+      l[7].i = 0x7FFFFFFF;
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(64) void k_topk_stage2(const Cand *__restrict__ cand, int32_t k, int32_t *__restrict__ out) {
+  const int rowi = blockIdx.x, lane = threadIdx.x;
+  // lane = segment * 8 + rank; ranks >= k were not written by stage 1
+  Cand mine = cand[(size_t)rowi * TOPK_SEGS * 8 + lane];
+  if ((lane & 7) >= k) {
+    mine.v = -__builtin_inff();
+    mine.i = 0x7FFFFFFF;
+  }
+  for (int p = 0; p < k; ++p) {
+    Cand best = mine;
+    for (int off = 32; off > 0; off >>= 1) {
+      Cand o;
+      o.v = __shfl_xor(best.v, off);
+      o.i = __shfl_xor(best.i, off);
+      if (before(o, best)) best = o;
+    }
+    if (lane == 0) out[(size_t)rowi * k + p] = best.i;
+    if (mine.i == best.i) {
+      mine.v = -__builtin_inff();
+      mine.i = 0x7FFFFFFF;
+    }
+  }
+}
+
+hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k, int32_t *d_topk,
+                       void *d_cand, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
+  const size_t esz = dtype_size(dtype);
+  if (k <= 8 && V >= TOPK_SEGS * k && d_cand != nullptr) {
+    for (int r0 = 0; r0 < rows; r0 += TR_MAX_NODES) { // the candidate scratch holds TR_MAX_NODES rows
+      const int nr = rows - r0 < TR_MAX_NODES ? rows - r0 : TR_MAX_NODES;
+      const char *src = (const char *)logits + (size_t)r0 * V * esz;
+      if (dtype == TR_BF16)
+        hipLaunchKernelGGL(k_topk_stage1<bf16_t>, dim3(nr, TOPK_SEGS), dim3(TOPK1_THREADS), 0, st, (const bf16_t *)src, V,
+                           k, (Cand *)d_cand);
+      else
+        hipLaunchKernelGGL(k_topk_stage1<float>, dim3(nr, TOPK_SEGS), dim3(TOPK1_THREADS), 0, st, (const float *)src, V,
+                           k, (Cand *)d_cand);
+      hipLaunchKernelGGL(k_topk_stage2, dim3(nr), dim3(64), 0, st, (const Cand *)d_cand, k, d_topk + (size_t)r0 * k);
+    }
+    return hipGetLastError();
+  }
   if (dtype == TR_BF16)
     hipLaunchKernelGGL(k_topk<bf16_t>, dim3(rows), dim3(TOPK_THREADS), 0, st, (const bf16_t *)logits, V, k, d_topk);
   else
     hipLaunchKernelGGL(k_topk<float>, dim3(rows), dim3(TOPK_THREADS), 0, st, (const float *)logits, V, k, d_topk);
   return hipGetLastError();
 }
+
+size_t topk_scratch_bytes() { return (size_t)TR_MAX_NODES * TOPK_SEGS * 8 * sizeof(Cand); }
 
 // ---------------------------------------------------------------------------------------------
 // Matrix update (Section 3.3): M[S[i], :] = topk[i, :] for every node.  A token that occurs more

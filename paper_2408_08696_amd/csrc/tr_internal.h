@@ -84,6 +84,7 @@ struct Workspace {
   size_t part_ml;  // float  [SPLITS, NP, H, 2] attention split partials: running max, sum
   size_t part_acc; // float  [SPLITS, NP, H, hd]
   size_t ypart;    // float  [GEMM_MAX_SPLITS, NP, d] K-split partial sums of o_proj / down_proj
+  size_t ssq;      // float  [NP, ceil(d/1024)] per-row partial sums of squares of the residual stream
   size_t total;
 };
 constexpr int NP = TR_MAX_NODES;
@@ -130,6 +131,7 @@ struct tr_ctx {
   tr::TreeDev chain;     // chain of TR_MAX_NODES nodes (prefill chunks)
   void *d_tree_blob;     // backing store of both trees
   int32_t *d_step_L;     // committed length at the start of the current accept/update
+  void *d_topk_cand;     // per-segment top-k candidates (two-stage top-k)
   int32_t h_depth[TR_MAX_NODES];
   tr::Profiler prof;
 };
@@ -138,8 +140,10 @@ namespace tr {
 
 // --- integer kernels (tr_int_kernels.hip) -------------------------------------------------------
 hipError_t launch_build_tree(const tr_ctx *c, const int32_t *d_root, int32_t *d_S, hipStream_t s);
+// d_cand: scratch of topk_scratch_bytes() owned by the context (may be NULL: slower one-kernel path)
 hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k,
-                       int32_t *d_topk, hipStream_t s);
+                       int32_t *d_topk, void *d_cand, hipStream_t s);
+size_t topk_scratch_bytes();
 hipError_t launch_matrix_update(const tr_ctx *c, const int32_t *d_S, const int32_t *d_topk, hipStream_t s);
 hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t *d_S,
                                 const int32_t *d_topk, tr_step_out *d_out, hipStream_t s);

@@ -34,7 +34,27 @@ struct GemmArgs {
   size_t split_stride; // floats between consecutive partial results
   bf16_t *h_frag;
   int32_t mode;
+  // optional RMS scale applied to output row r: 1/sqrt(sum_c row_ssq[r*n_ssq + c] / norm_dim + eps)
+  const float *row_ssq;
+  int32_t n_ssq, norm_dim;
+  float eps;
+  int32_t total_tiles;  // sum of seg[i].out_tiles
+  int32_t tiles_per_wg; // P, from gemm_choose
 };
+
+// Fills g.total_tiles, g.tiles_per_wg and g.splits (<= max_splits; 1 for GEMM_SWIGLU).
+void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, const int32_t *seg_tiles, int32_t n_seg, bool swiglu,
+                 int32_t max_splits, int32_t *out_p, int32_t *out_splits);
+inline void gemm_plan(GemmArgs &g, int32_t max_splits) {
+  int32_t st[3] = {0, 0, 0}, total = 0;
+  for (int i = 0; i < g.n_seg; ++i) {
+    st[i] = g.seg[i].out_tiles;
+    total += st[i];
+  }
+  g.total_tiles = total;
+  gemm_choose(g.n, g.K, total, st, g.n_seg, g.mode == GEMM_SWIGLU, g.mode == GEMM_SWIGLU ? 1 : max_splits,
+              &g.tiles_per_wg, &g.splits);
+}
 
 bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O);
 hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st);
