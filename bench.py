@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--no-ar", action="store_true", help="skip the 1-node autoregressive comparison run")
     ap.add_argument("--no-hot", action="store_true", help="skip the hot-start rerun")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times (reference for rocprofv3 --pmc byte counters)")
     return ap.parse_args()
 
 
@@ -127,11 +129,21 @@ def main():
                  for k, v in prof.items()}
     gu_launches, gu_ms = prof["gate_up_swiglu"]
     gu_bytes = 2 * sh.d_ffn * sh.d_model * 2                       # gate + up weights, bf16, read once
-    gu_avg_s = gu_ms / gu_launches * 1e-3
+    empty_ms = prof["empty_bracket"][1] / prof["empty_bracket"][0]  # cost of an event pair around nothing
+    gu_avg_s = (gu_ms / gu_launches - empty_ms) * 1e-3
     achieved = gu_bytes / gu_avg_s / 1e9
     roofline = {"kernel": "gate_up_swiglu (k_gemm_mfma, fused gate/up projection + SwiGLU)", "bound": "hbm",
                 "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
-                "traffic": None, "avg_launch_us": gu_avg_s * 1e6, "algorithmic_bytes_per_launch": gu_bytes}
+                "traffic": None, "avg_launch_us": gu_avg_s * 1e6, "algorithmic_bytes_per_launch": gu_bytes,
+                "event_bracket_overhead_us": empty_ms * 1e3}
+    # HBM bytes per launch of this kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, if a summary for this
+    # workload has been recorded under profiles/ (bench.py cannot run the profiler on itself)
+    pmc = os.path.join(ROOT, "profiles", f"gate_up_swiglu_{sh.name}_tree80_pmc.txt")
+    if os.path.exists(pmc):
+        for line in open(pmc):
+            if line.startswith("traffic_bytes_per_launch:"):
+                roofline["traffic"] = float(line.split(":")[1])
+                roofline["traffic_source"] = os.path.relpath(pmc, ROOT)
     wbytes = sh.weight_params() * 2
     step_roofline = {"weight_bytes": wbytes, "ms_at_peak_hbm": wbytes / (PEAK_HBM_GBS * 1e9) * 1e3,
                      "frac": wbytes / (PEAK_HBM_GBS * 1e9) * 1e3 / ms_step}
@@ -169,6 +181,29 @@ def main():
         if "tokens_per_s_hot_start" in out:
             out["speedup_vs_ar_hot_start"] = out["tokens_per_s_hot_start"] / out["ar_tokens_per_s"]
         del ar
+
+    # achievable streaming rate on this machine: the library's plain read kernel over 32 distinct 256 MiB
+    # buffers (8 GiB, far beyond the 256 MB Infinity Cache), timed with events on the same stream
+    bufs = [torch.ones(1 << 26, dtype=torch.float32, device="cuda") for _ in range(32)]
+    for b_ in bufs[:4]:
+        tr.op_stream(b_)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for b_ in bufs:
+        tr.op_stream(b_)
+    e1.record()
+    torch.cuda.synchronize()
+    stream_gbs = len(bufs) * bufs[0].numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    out["stream_read_ceiling_GBs"] = stream_gbs
+    out["roofline"]["frac_of_stream_ceiling"] = achieved / stream_gbs
+    out["step_roofline"]["frac_of_stream_ceiling"] = wbytes / (stream_gbs * 1e9) * 1e3 / ms_step
+    if a.calibrate_copy:
+        # a copy of known size (256 MiB read + 256 MiB written) for calibrating rocprofv3 --pmc byte counters
+        for _ in range(4):
+            tr.op_stream(bufs[0], bufs[1])
+        torch.cuda.synchronize()
+        out["calibrate_copy_bytes_each_way"] = bufs[0].numel() * 4
+    del bufs
 
     if a.cpu_steps > 0:
         out["cpu_baseline"] = cpu_baseline(sh, w, tmpl, prompt, a.cpu_steps, synth)

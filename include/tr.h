@@ -241,12 +241,22 @@ tr_status tr_op_linear(tr_ctx *ctx, const void *d_x, const void *d_w, int32_t dt
                        void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Measurement aid: one plain streaming pass over `bytes` (multiple of 16) of [device] memory with the
+ * same load instructions the weight-streaming kernels use — read-only if d_dst is NULL, else a copy
+ * to d_dst.  Gives the achievable HBM streaming rate on the machine at hand and a kernel of known
+ * traffic to calibrate hardware byte counters against.
+ */
+tr_status tr_op_stream(const void *d_src, void *d_dst, size_t bytes, void *stream);
+
+/*
  * Per-kernel timing for the time-allocation breakdown (the paper's Figure 6 reports the same
  * split: retrieval / model forward / verification / update).  While enabled, every kernel the
  * step calls launch is bracketed by HIP events on the caller's stream; tr_profile_read
  * synchronises the device, sums elapsed times per kernel class, returns up to max_entries
  * entries ([host]) and resets the counters.  Enabling allocates the event pool (the only
- * allocation after tr_create); events beyond the pool are silently not recorded.
+ * allocation after tr_create); events beyond the pool are silently not recorded.  The entry
+ * "empty_bracket" times an event pair with no kernel between (once per step): subtract its mean from
+ * a launch's elapsed time to get the kernel's own duration.
  */
 typedef struct {
   char name[24];

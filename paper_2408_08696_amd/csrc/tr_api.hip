@@ -228,6 +228,7 @@ tr_status tr_accept_and_update(tr_ctx *c, tr_kv *kv, const int32_t *d_S, const i
   if (s != TR_OK) return s;
   if ((int64_t)kv->len_bound + c->tree.n_nodes > kv->capacity) return TR_ECAPACITY;
   hipStream_t st = as_stream(stream);
+  { ProfScope empty(&c->prof, PC_EMPTY, st); } // an event pair around nothing: the bracket's own cost
   {
     ProfScope ps(&c->prof, PC_ACCEPT, st);
     if (launch_accept_update(c, kv, d_S, d_topk, d_out, st) != hipSuccess) return TR_EHIP;
@@ -309,6 +310,11 @@ tr_status tr_pack_weight(const void *d_src, void *d_dst, int32_t out_f, int32_t 
              : TR_EHIP;
 }
 
+tr_status tr_op_stream(const void *d_src, void *d_dst, size_t bytes, void *stream) {
+  if (d_src == nullptr || bytes == 0 || bytes % 16 != 0) return TR_EINVAL;
+  return launch_stream(d_src, d_dst, bytes, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;
+}
+
 tr_status tr_profile_enable(tr_ctx *c, int32_t enable) {
   if (c == nullptr) return TR_EINVAL;
   Profiler &p = c->prof;
@@ -326,7 +332,7 @@ tr_status tr_profile_enable(tr_ctx *c, int32_t enable) {
 tr_status tr_profile_read(tr_ctx *c, tr_profile_entry *h, int32_t max_entries, int32_t *n_entries) {
   static const char *const names[PC_COUNT] = {"build_tree", "embed_rope_table", "rmsnorm", "qkv_proj", "rope_kv_write",
                                               "tree_attention", "o_proj", "gate_up_swiglu", "down_proj", "lm_head",
-                                              "topk", "accept_update_compact"};
+                                              "topk", "accept_update_compact", "empty_bracket"};
   if (c == nullptr || h == nullptr || n_entries == nullptr || max_entries < 0) return TR_EINVAL;
   Profiler &p = c->prof;
   if (hipDeviceSynchronize() != hipSuccess) return TR_EHIP;

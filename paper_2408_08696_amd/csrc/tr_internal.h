@@ -97,7 +97,7 @@ Workspace plan_workspace(const tr_model &m);
 // optional per-kernel-class event timing
 // ---------------------------------------------------------------------------------------------
 enum ProfCat { PC_BUILD = 0, PC_EMBED, PC_NORM, PC_QKV, PC_ROPE, PC_ATTN, PC_OPROJ, PC_GATEUP, PC_DOWN, PC_LMHEAD,
-               PC_TOPK, PC_ACCEPT, PC_COUNT };
+               PC_TOPK, PC_ACCEPT, PC_EMPTY, PC_COUNT };
 struct Profiler {
   static constexpr int MAX_PAIRS = 8192;
   hipEvent_t *ev = nullptr; // 2 * MAX_PAIRS
@@ -148,6 +148,7 @@ hipError_t launch_matrix_update(const tr_ctx *c, const int32_t *d_S, const int32
 hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t *d_S,
                                 const int32_t *d_topk, tr_step_out *d_out, hipStream_t s);
 hipError_t launch_advance_len(int32_t *d_len, int32_t by, hipStream_t s);
+hipError_t launch_stream(const void *src, void *dst, size_t bytes, hipStream_t s);
 
 // --- forward pass (tr_forward.hip) -----------------------------------------------------------------
 // Runs rows `tokens` through the model.  `write_logits` may be NULL (no LM head).

@@ -79,6 +79,7 @@ _SIGS = {
     "tr_op_linear": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                      C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
     "tr_pack_weight": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
+    "tr_op_stream": [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
     "tr_profile_enable": [C.c_void_p, C.c_int32],
     "tr_profile_read": [C.c_void_p, C.POINTER(ProfileEntry), C.c_int32, C.POINTER(C.c_int32)],
 }
@@ -215,6 +216,11 @@ class Context:
         _check(lib().tr_op_linear(self._h, _ptr(d_x), _ptr(d_w), dt, TR_PACKED if packed else TR_ROW_MAJOR,
                                   d_x.shape[0], d_x.shape[1], d_w.shape[0], splits, _ptr(d_y), _ptr(ws),
                                   0 if ws is None else ws.numel() * ws.element_size(), _stream()), "tr_op_linear")
+
+
+def op_stream(src, dst=None) -> None:
+    """Plain streaming read of `src` (or copy into `dst`) through the library's streaming kernel."""
+    _check(lib().tr_op_stream(src.data_ptr(), _ptr(dst), src.numel() * src.element_size(), _stream()), "tr_op_stream")
 
 
 def pack_weight(w):
