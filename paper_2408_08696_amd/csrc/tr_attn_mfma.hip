@@ -178,29 +178,44 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
 }
 
 // out[node, h, :] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max m); splits without visible keys
-// (l_s == 0) are skipped.  Block (node, head), 128 threads = head_dim.
-__global__ __launch_bounds__(128) void k_attn_merge(const float *__restrict__ part_ml, const float *__restrict__ part_acc,
-                                                    int32_t H, int32_t nsplit, bf16_t *__restrict__ out,
+// (l_s == 0) contribute nothing.  Block (8 nodes, head), 32 threads x 4 features per node; all loads of a
+// thread are issued before any arithmetic.
+__global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ part_ml, const float *__restrict__ part_acc,
+                                                    int32_t H, int32_t n, int32_t nsplit, bf16_t *__restrict__ out,
                                                     int32_t out_row_tiles) {
-  const int node = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
-  float M = NEG_BIG;
-  for (int s = 0; s < nsplit; ++s) {
-    const size_t row = ((size_t)s * H + h) * NP + node;
-    if (part_ml[row * 2 + 1] > 0.f) M = fmaxf(M, part_ml[row * 2]);
-  }
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
-    const size_t row = ((size_t)s * H + h) * NP + node;
-    const float l = part_ml[row * 2 + 1];
-    if (l > 0.f) {
-      const float w = exp2f(part_ml[row * 2] - M);
-      den += w * l;
-      num += w * part_acc[row * 128 + d];
+  const int node = blockIdx.x * 8 + (threadIdx.x >> 5), h = blockIdx.y, d = (threadIdx.x & 31) * 4;
+  if (node >= n) return;
+  float2 ml[ATTN_MAX_SPLITS];
+  float4 av[ATTN_MAX_SPLITS];
+#pragma unroll
+  for (int s = 0; s < ATTN_MAX_SPLITS; ++s) {
+    if (s < nsplit) {
+      const size_t row = ((size_t)s * H + h) * NP + node;
+      ml[s] = *reinterpret_cast<const float2 *>(part_ml + row * 2);
+      av[s] = *reinterpret_cast<const float4 *>(part_acc + row * 128 + d);
     }
   }
+  float M = NEG_BIG;
+#pragma unroll
+  for (int s = 0; s < ATTN_MAX_SPLITS; ++s)
+    if (s < nsplit && ml[s].y > 0.f) M = fmaxf(M, ml[s].x);
+  float den = 0.f;
+  float4 num = float4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < ATTN_MAX_SPLITS; ++s) {
+    if (s < nsplit && ml[s].y > 0.f) {
+      const float w = exp2f(ml[s].x - M);
+      den += w * ml[s].y;
+      num.x += w * av[s].x; num.y += w * av[s].y; num.z += w * av[s].z; num.w += w * av[s].w;
+    }
+  }
+  const float inv = 1.0f / den;
+  ushort4 o;
+  o.x = f32_to_bf16(num.x * inv); o.y = f32_to_bf16(num.y * inv);
+  o.z = f32_to_bf16(num.z * inv); o.w = f32_to_bf16(num.w * inv);
   const size_t idx = out_row_tiles > 0 ? act_frag_index(node, h * 128 + d, out_row_tiles)
                                        : ((size_t)node * H + h) * 128 + d;
-  out[idx] = f32_to_bf16(num / den);
+  *reinterpret_cast<ushort4 *>(out + idx) = o;
 }
 
 bool attn_mfma_supported(int32_t hd, int32_t n) { return hd == 128 && n >= 1 && n <= TR_MAX_NODES; }
@@ -237,7 +252,8 @@ hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl,
   case 8: e = launch_attn_nt<8>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
   }
   if (e != hipSuccess || nsplit == 1) return e;
-  hipLaunchKernelGGL(k_attn_merge, dim3(n, H), dim3(128), 0, st, part_ml, part_acc, H, nsplit, out, out_row_tiles);
+  hipLaunchKernelGGL(k_attn_merge, dim3((n + 7) / 8, H), dim3(256), 0, st, part_ml, part_acc, H, n, nsplit, out,
+                     out_row_tiles);
   return hipGetLastError();
 }
 

@@ -148,48 +148,62 @@ __global__ __launch_bounds__(256) void k_swiglu(const float *__restrict__ gu, in
 // Rotary embedding + KV write.  Block (n, head) over the concatenated [q heads | k heads | v heads].
 // Rotated q -> q[n, h, :]; rotated k -> K[layer][h][L+n][:]; v -> V[layer][h][:][L+n].
 // ---------------------------------------------------------------------------------------------
+constexpr int ROPE_HPB = 8; // heads per block
 template <typename T>
-__global__ __launch_bounds__(128) void k_rope_kv(const float *__restrict__ qkv, int32_t n_part, size_t part_stride,
+__global__ __launch_bounds__(256) void k_rope_kv(const float *__restrict__ qkv, int32_t n_part, size_t part_stride,
                                                  const float *__restrict__ rope, int32_t H, int32_t Hkv, int32_t hd,
                                                  int32_t cap,
                                                  const int32_t *__restrict__ d_len, T *__restrict__ q,
                                                  T *__restrict__ Kl, T *__restrict__ Vl, int32_t tiled) {
-  const int n = blockIdx.x, hh = blockIdx.y;
+  const int n = blockIdx.x;
   const int half = hd / 2;
-  const int width = (H + 2 * Hkv) * hd;
-  const float *src = qkv + (size_t)n * width + (size_t)hh * hd;
+  const int heads = H + 2 * Hkv;
+  const int width = heads * hd;
   const int pos = *d_len + n;
-  // the projection may arrive as n_part K-split partial sums, added here in split order
-  auto val = [&](int i) {
-    float v = src[i];
-    for (int s = 1; s < n_part; ++s) v += src[(size_t)s * part_stride + i];
-    return v;
-  };
-  if (hh < H + Hkv) {
-    for (int i = threadIdx.x; i < half; i += blockDim.x) {
-      const float c = rope[(size_t)n * hd + i], s = rope[(size_t)n * hd + half + i];
-      const float a = val(i), b = val(i + half);
-      const T ra = from_f32<T>(a * c - b * s), rb = from_f32<T>(b * c + a * s);
-      if (hh < H) {
-        T *dst = q + ((size_t)n * H + hh) * hd;
-        dst[i] = ra;
-        dst[i + half] = rb;
-      } else if (tiled) {
+  const float *row = qkv + (size_t)n * width;
+  // work item = (head, i): elements i and i + hd/2 of that head (a rotation pair for q and k heads)
+  const int items = ROPE_HPB * half;
+  for (int it = threadIdx.x; it < items; it += 256) {
+    const int hh = blockIdx.y * ROPE_HPB + it / half, i = it % half;
+    if (hh >= heads) break;
+    const float *src = row + (size_t)hh * hd;
+    // the projection may arrive as n_part K-split partial sums, added here in split order
+    float a = src[i], b = src[i + half];
+    for (int s = 1; s < n_part; ++s) {
+      a += src[(size_t)s * part_stride + i];
+      b += src[(size_t)s * part_stride + i + half];
+    }
+    if (hh < H + Hkv) {
+      const float c = rope[(size_t)n * hd + i], sn = rope[(size_t)n * hd + half + i];
+      const float ra = a * c - b * sn, rb = b * c + a * sn;
+      a = ra;
+      b = rb;
+    }
+    const T ta = from_f32<T>(a), tb = from_f32<T>(b);
+    if (hh < H) {
+      T *dst = q + ((size_t)n * H + hh) * hd;
+      dst[i] = ta;
+      dst[i + half] = tb;
+    } else if (hh < H + Hkv) {
+      if (tiled) {
         T *dst = Kl + (size_t)(hh - H) * cap * hd;
-        dst[kv_k_index(pos, i)] = ra;
-        dst[kv_k_index(pos, i + half)] = rb;
+        dst[kv_k_index(pos, i)] = ta;
+        dst[kv_k_index(pos, i + half)] = tb;
       } else {
         T *dst = Kl + ((size_t)(hh - H) * cap + pos) * hd;
-        dst[i] = ra;
-        dst[i + half] = rb;
+        dst[i] = ta;
+        dst[i + half] = tb;
+      }
+    } else {
+      T *dst = Vl + (size_t)(hh - H - Hkv) * hd * cap;
+      if (tiled) {
+        dst[kv_v_index(pos, i)] = ta;
+        dst[kv_v_index(pos, i + half)] = tb;
+      } else {
+        dst[(size_t)i * cap + pos] = ta;
+        dst[(size_t)(i + half) * cap + pos] = tb;
       }
     }
-  } else if (tiled) {
-    T *dst = Vl + (size_t)(hh - H - Hkv) * hd * cap;
-    for (int i = threadIdx.x; i < hd; i += blockDim.x) dst[kv_v_index(pos, i)] = from_f32<T>(val(i));
-  } else {
-    T *dst = Vl + (size_t)(hh - H - Hkv) * hd * cap + pos;
-    for (int i = threadIdx.x; i < hd; i += blockDim.x) dst[(size_t)i * cap] = from_f32<T>(val(i));
   }
 }
 
@@ -334,7 +348,7 @@ static hipError_t forward_generic(const tr_model &m, const tr_kv &kv, const Tree
     }
     {
       ProfScope ps(prof, PC_ROPE, st);
-      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, 1, (size_t)0, rope, H, Hkv, hd,
+      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, (H + 2 * Hkv + ROPE_HPB - 1) / ROPE_HPB), dim3(256), 0, st, qkv, 1, (size_t)0, rope, H, Hkv, hd,
                          kv.capacity, kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, kv.layout);
       TR_TRY(hipGetLastError());
     }
@@ -510,7 +524,7 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
     }
     {
       ProfScope ps(prof, PC_ROPE, st);
-      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, H + 2 * Hkv), dim3(128), 0, st, qkv, qkv_parts, qstride, rope, H, Hkv,
+      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, (H + 2 * Hkv + ROPE_HPB - 1) / ROPE_HPB), dim3(256), 0, st, qkv, qkv_parts, qstride, rope, H, Hkv,
                          hd, kv.capacity, kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz,
                          kv.layout);
       TR_TRY(hipGetLastError());
