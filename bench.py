@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--no-hot", action="store_true", help="skip the hot-start rerun")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--sweep-nodes", default="",
+                    help="comma-separated tree sizes: time the step for each (breadth-first prefixes of the 128-node "
+                         "template) instead of the headline run, and print one JSON line with the table")
     return ap.parse_args()
 
 
@@ -110,6 +113,33 @@ def main():
     M0 = synth.init_matrix(sh.vocab, K)
     total_steps = a.warmup + a.steps + a.profile_steps
     cap = a.prompt_len + total_steps * tmpl.n_layers + tmpl.n_nodes + 64
+
+    if a.sweep_nodes:
+        # Step time versus tree size (Section 5.1 / Figure 3a asks where verifying more nodes stops being
+        # as cheap as one token): same model, prompt and KV length, one engine per tree size.
+        model = tr.ModelDesc(sh, w)
+        del w
+        rows = []
+        for nn in [int(v) for v in a.sweep_nodes.split(",")]:
+            t = synth.prefix_template(nn)
+            e = tr.Engine(sh, None, t, k=K, capacity=a.prompt_len + (a.warmup + a.steps) * t.n_layers + 256,
+                          keep_logits=False, model=model)
+            e.ctx.matrix_load(M0)
+            e.prefill(prompt)
+            timed_steps(e, torch, a.warmup)
+            dts, tk = timed_steps(e, torch, a.steps)
+            rows.append({"n_nodes": nn, "n_layers": t.n_layers, "ms_per_step": dts / a.steps * 1e3,
+                         "steps_per_s": a.steps / dts, "mat": tk / a.steps})
+            del e
+        base = rows[0]["ms_per_step"]
+        for r in rows:
+            r["cost_vs_first"] = r["ms_per_step"] / base
+        print(json.dumps({"metric": "TR step time vs tree size", "unit": "ms/step", "n_gpus": 1, "steps": a.steps,
+                          "warmup": a.warmup, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": f"{sh.name}-shape random-init Llama bf16, batch 1, prompt "
+                                                 f"{a.prompt_len}, breadth-first prefixes of the 128-node template"},
+                          "sweep": rows}))
+        return
 
     eng = tr.Engine(sh, w, tmpl, k=K, capacity=cap, keep_logits=False)
     eng.ctx.matrix_load(M0)

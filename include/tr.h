@@ -153,6 +153,16 @@ tr_status tr_create(int32_t V, int32_t k, const tr_tree_template *tree, tr_ctx *
 tr_status tr_destroy(tr_ctx *ctx);
 
 /*
+ * Variants of the matrix update the paper compares (Section 5.2 "Update Strategies", Appendix A.5, and
+ * "Effect of Rejected Tokens", Table 4).  Default: TR_UPDATE_LAST over all nodes.  TR_UPDATE_FIRST lets the
+ * first occurrence of a repeated token own the row; | TR_UPDATE_ACCEPTED_ONLY restricts the update to the
+ * nodes of the accepted path (first / last then refer to occurrences on that path).  tr_op_matrix_update
+ * has no accepted path and ignores TR_UPDATE_ACCEPTED_ONLY.  Errors: TR_EINVAL (NULL, unknown bits).
+ */
+typedef enum { TR_UPDATE_LAST = 0, TR_UPDATE_FIRST = 1, TR_UPDATE_ACCEPTED_ONLY = 2 } tr_update_mode;
+tr_status tr_set_update_mode(tr_ctx *ctx, int32_t mode);
+
+/*
  * Copy the whole matrix from / to [host] memory, int32 [V * k], synchronously (hot start,
  * Section 3.1: the matrix persists across queries and may be saved and restored).
  */

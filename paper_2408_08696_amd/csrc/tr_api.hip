@@ -175,6 +175,12 @@ tr_status tr_destroy(tr_ctx *c) {
   return (e1 == hipSuccess && e2 == hipSuccess) ? TR_OK : TR_EHIP;
 }
 
+tr_status tr_set_update_mode(tr_ctx *c, int32_t mode) {
+  if (c == nullptr || mode < 0 || mode > (TR_UPDATE_FIRST | TR_UPDATE_ACCEPTED_ONLY)) return TR_EINVAL;
+  c->update_mode = mode;
+  return TR_OK;
+}
+
 tr_status tr_matrix_load(tr_ctx *c, const int32_t *h_M) {
   if (c == nullptr || h_M == nullptr) return TR_EINVAL;
   const size_t cnt = (size_t)c->V * c->k;

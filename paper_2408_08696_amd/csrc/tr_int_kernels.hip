@@ -230,18 +230,28 @@ size_t topk_scratch_bytes() { return (size_t)TR_MAX_NODES * TOPK_SEGS * 8 * size
 // than once is written by its last occurrence only (Appendix A.5 "Last"), which makes the result
 // independent of thread scheduling.
 // ---------------------------------------------------------------------------------------------
+// mode: TR_UPDATE_LAST / TR_UPDATE_FIRST (which occurrence of a repeated token owns the row), optionally
+// | TR_UPDATE_ACCEPTED_ONLY (only nodes on the accepted path are eligible, e0/e1 = their bit mask).
 __device__ inline void scatter_rows(int32_t *__restrict__ M, int32_t k, int n_nodes, const int32_t *sS,
-                                    const int32_t *__restrict__ topk, int i) {
+                                    const int32_t *__restrict__ topk, int i, int mode, uint64_t e0, uint64_t e1) {
   if (i >= n_nodes) return;
+  const bool restricted = (mode & TR_UPDATE_ACCEPTED_ONLY) != 0;
+  auto eligible = [&](int j) { return !restricted || ((j < 64 ? (e0 >> j) : (e1 >> (j - 64))) & 1ull); };
+  if (!eligible(i)) return;
   const int tok = sS[i];
-  for (int j = i + 1; j < n_nodes; ++j)
-    if (sS[j] == tok) return; // a later occurrence owns the row
+  if ((mode & 1) == TR_UPDATE_FIRST) {
+    for (int j = 0; j < i; ++j)
+      if (sS[j] == tok && eligible(j)) return; // an earlier occurrence owns the row
+  } else {
+    for (int j = i + 1; j < n_nodes; ++j)
+      if (sS[j] == tok && eligible(j)) return; // a later occurrence owns the row
+  }
   for (int c = 0; c < k; ++c) M[(size_t)tok * k + c] = topk[(size_t)i * k + c];
 }
 
 __global__ __launch_bounds__(TR_MAX_NODES) void k_matrix_update(int32_t *__restrict__ M, int32_t V, int32_t k,
                                                                 int32_t n_nodes, const int32_t *__restrict__ S,
-                                                                const int32_t *__restrict__ topk) {
+                                                                const int32_t *__restrict__ topk, int32_t mode) {
   __shared__ int32_t sS[TR_MAX_NODES];
   const int i = threadIdx.x;
   if (i < n_nodes) {
@@ -249,12 +259,12 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_matrix_update(int32_t *__restr
     sS[i] = t < 0 ? 0 : (t >= V ? V - 1 : t);
   }
   __syncthreads();
-  scatter_rows(M, k, n_nodes, sS, topk, i);
+  scatter_rows(M, k, n_nodes, sS, topk, i, mode & 1, 0ull, 0ull); // no path here: every node is eligible
 }
 
 hipError_t launch_matrix_update(const tr_ctx *c, const int32_t *d_S, const int32_t *d_topk, hipStream_t st) {
   hipLaunchKernelGGL(k_matrix_update, dim3(1), dim3(TR_MAX_NODES), 0, st, c->d_M, c->V, c->k,
-                     c->tree.n_nodes, d_S, d_topk);
+                     c->tree.n_nodes, d_S, d_topk, c->update_mode);
   return hipGetLastError();
 }
 
@@ -271,7 +281,7 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_accept_update(int32_t *__restr
                                                                 const int32_t *__restrict__ topk,
                                                                 int32_t *__restrict__ d_len,
                                                                 int32_t *__restrict__ step_L,
-                                                                tr_step_out *__restrict__ out) {
+                                                                tr_step_out *__restrict__ out, int32_t mode) {
   __shared__ int32_t sS[TR_MAX_NODES];
   __shared__ int32_t sOut[TR_MAX_NODES];
   __shared__ uint64_t mbits[2];
@@ -324,7 +334,9 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_accept_update(int32_t *__restr
     *d_len = L + a + 1;
     out->kv_len = L + a + 1;
   }
-  scatter_rows(M, k, t.n_nodes, sS, topk, i);
+  // best_key is final since the barrier above; every thread derives the winner's path mask from it
+  const int win = 255 - (best_key & 255);
+  scatter_rows(M, k, t.n_nodes, sS, topk, i, mode, t.anc[2 * win], t.anc[2 * win + 1]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -365,7 +377,7 @@ __global__ __launch_bounds__(256) void k_compact_kv(T *__restrict__ K, T *__rest
 hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t *d_S, const int32_t *d_topk,
                                 tr_step_out *d_out, hipStream_t st) {
   hipLaunchKernelGGL(k_accept_update, dim3(1), dim3(TR_MAX_NODES), 0, st, c->d_M, c->V, c->k, c->tree, d_S,
-                     d_topk, kv->d_len, c->d_step_L, d_out);
+                     d_topk, kv->d_len, c->d_step_L, d_out, c->update_mode);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int blocks = kv->n_layers * kv->n_kv_heads;

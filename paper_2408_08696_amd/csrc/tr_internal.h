@@ -132,6 +132,7 @@ struct tr_ctx {
   void *d_tree_blob;     // backing store of both trees
   int32_t *d_step_L;     // committed length at the start of the current accept/update
   void *d_topk_cand;     // per-segment top-k candidates (two-stage top-k)
+  int32_t update_mode;   // tr_update_mode bits
   int32_t h_depth[TR_MAX_NODES];
   tr::Profiler prof;
 };

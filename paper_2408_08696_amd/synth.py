@@ -285,6 +285,19 @@ def wide128() -> TreeTemplate:
     return t
 
 
+def prefix_template(n: int) -> TreeTemplate:
+    """The first n nodes (breadth-first order) of wide128: a breadth-first prefix of a tree is a tree.
+    Used for the step-time-versus-tree-size sweep (the paper's Figure 3a varies breadth the same way)."""
+    base = wide128()
+    assert 1 <= n <= base.n_nodes
+    parent, rank = base.parent[:n].copy(), base.rank[:n].copy()
+    depth = np.zeros(n, np.int64)
+    for i in range(1, n):
+        depth[i] = depth[parent[i]] + 1
+    sizes = tuple(int(c) for c in np.bincount(depth))
+    return TreeTemplate(f"prefix{n}", parent, rank, len(sizes), sizes)
+
+
 TEMPLATES = {
     "tree80": tree80, "tree81": tree81, "tree15": tree15, "tree15_alt": tree15_alt,
     "single": single, "wide128": wide128,

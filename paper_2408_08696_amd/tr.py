@@ -20,6 +20,7 @@ TR_OK, TR_EINVAL, TR_ETEMPLATE, TR_ENOMEM, TR_EHIP, TR_ECAPACITY, TR_ESTATE = 0,
 TR_F32, TR_BF16 = 0, 1
 TR_ROW_MAJOR, TR_PACKED = 0, 1
 TR_KV_PLAIN, TR_KV_TILED = 0, 1
+TR_UPDATE_LAST, TR_UPDATE_FIRST, TR_UPDATE_ACCEPTED_ONLY = 0, 1, 2
 DTYPES = {"f32": TR_F32, "bf16": TR_BF16}
 
 
@@ -62,6 +63,7 @@ STEP_OUT_INTS = C.sizeof(StepOut) // 4
 _SIGS = {
     "tr_create": [C.c_int32, C.c_int32, C.POINTER(TreeTemplate), C.POINTER(C.c_void_p)],
     "tr_destroy": [C.c_void_p],
+    "tr_set_update_mode": [C.c_void_p, C.c_int32],
     "tr_matrix_load": [C.c_void_p, C.c_void_p],
     "tr_matrix_store": [C.c_void_p, C.c_void_p],
     "tr_build_tree": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
@@ -152,6 +154,9 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def set_update_mode(self, mode: int) -> None:
+        _check(lib().tr_set_update_mode(self._h, mode), "tr_set_update_mode")
 
     def matrix_load(self, M: np.ndarray) -> None:
         M = np.ascontiguousarray(M, dtype=np.int32)

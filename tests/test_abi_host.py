@@ -74,6 +74,7 @@ def test_null_arguments(lib):
     assert lib.tr_accept_and_update(None, None, None, None, None, None, None) == tr.TR_EINVAL
     assert lib.tr_prefill(None, None, None, None, 0, None, 0, None) == tr.TR_EINVAL
     assert lib.tr_op_topk(None, None, 0, 0, None, None) == tr.TR_EINVAL
+    assert lib.tr_set_update_mode(None, 0) == tr.TR_EINVAL
 
 
 def test_default_templates_are_accepted_by_the_host_check():

@@ -65,14 +65,16 @@ def test_tiny_fp32_free_running(tmpl_name):
 @pytest.mark.parametrize("shape_name,tmpl_name", [("tiny_bf16", "tree80"), ("tiny_gqa_bf16", "tree80"),
                                                   ("tiny_bf16", "tree81"), ("tiny_bf16", "wide128"),
                                                   ("tiny_bf16", "single"), ("tiny", "tree80"),
-                                                  ("tiny_odd_bf16", "tree80"), ("tiny_bf16:rowmajor", "tree15")])
+                                                  ("tiny_odd_bf16", "tree80"), ("tiny_bf16:rowmajor", "tree15"),
+                                                  ("tiny_bf16", "prefix48"), ("tiny_gqa_bf16", "prefix97")])
 def test_small_shapes_lockstep(shape_name, tmpl_name):
     require_gpu()
     pack = None
     if shape_name.endswith(":rowmajor"):
         shape_name, pack = shape_name.split(":")[0], False    # bf16 through the generic kernels
     sh = synth.SHAPES[shape_name]
-    tmpl = synth.TEMPLATES[tmpl_name]()
+    tmpl = (synth.prefix_template(int(tmpl_name[6:])) if tmpl_name.startswith("prefix")
+            else synth.TEMPLATES[tmpl_name]())
     w = synth.make_weights(sh, seed=1)
     prompt = synth.zipf_prompt(sh.vocab, 150, seed=3, ngram=8).tolist()
     eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=512, pack=pack)

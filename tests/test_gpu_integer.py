@@ -122,11 +122,12 @@ def test_update_example_on_gpu(golden):
         assert M[tok].tolist() == [int(x) for x in g[f"expect_both {tok}"][0]]
 
 
-def _run_accept(t, S, topk, V=64, L=10, hd=32, layers=2, heads=2, dtype="f32"):
+def _run_accept(t, S, topk, V=64, L=10, hd=32, layers=2, heads=2, dtype="f32", mode=0):
     """Calls tr_accept_and_update on a small cache whose tree rows are tagged with their node
     index, returns (StepOut, M, k-cache, v-cache) with the caches in natural [.., pos, hd] order."""
     sh = synth.ModelShape("acc", layers, 64, heads, heads, hd, 64, V, dtype)
     ctx = tr.Context(V, topk.shape[1], t.parent, t.rank, t.n_layers)
+    ctx.set_update_mode(mode)
     kv = tr.KVDesc(sh, capacity=L + t.n_nodes + 4)
     kv.reset(L)
     n = t.n_nodes
@@ -196,3 +197,44 @@ def test_accept_update_compact_matches_oracle(name, kvmode):
         ctx.close()
     if name != "single":
         assert len(depths) >= min(3, tree.n_layers)
+
+
+@pytest.mark.parametrize("mode", [tr.TR_UPDATE_FIRST, tr.TR_UPDATE_ACCEPTED_ONLY,
+                                  tr.TR_UPDATE_FIRST | tr.TR_UPDATE_ACCEPTED_ONLY])
+def test_update_variants_match_oracle(mode):
+    """First-occurrence and accepted-only updates (Section 5.2, Appendix A.5, Table 4) against the
+    oracle's update_matrix on heavily duplicated node tokens."""
+    require_gpu()
+    t = synth.tree80()
+    tree = O.make_tree(t.parent, t.rank, K)
+    rng = np.random.default_rng(31)
+    for trial in range(25):
+        V = int(rng.choice([3, 6, 64]))
+        S = rng.integers(0, V, size=t.n_nodes)
+        topk = rng.integers(0, 64, size=(t.n_nodes, K))
+        n = int(rng.integers(0, t.n_nodes))
+        for i in range(1, len(tree.paths[n])):
+            topk[tree.paths[n][i - 1], 0] = S[tree.paths[n][i]]
+        say("update variant", mode, "trial", trial)
+        h, M, _, _, ctx = _run_accept(t, S, topk, mode=mode)
+        acc = O.accept(S, topk[:, 0], tree)
+        assert list(h.path[:h.n_emitted]) == acc.path
+        want = np.zeros((64, K), np.int64)
+        O.update_matrix(want, S, topk, "first" if mode & tr.TR_UPDATE_FIRST else "last",
+                        acc.path if mode & tr.TR_UPDATE_ACCEPTED_ONLY else None)
+        assert np.array_equal(M.astype(np.int64), want)
+        ctx.close()
+
+
+def test_update_example_first_on_gpu(golden):
+    require_gpu()
+    g = golden("update_strategies_example.txt")
+    S = np.array([int(x) for x in g["sequence"][0]], np.int32)
+    topk = np.array([[int(x) for x in g[f"out {i}"][0]] for i in range(5)], np.int32)
+    ctx = tr.Context(500, 4, [-1, 0, 1, 2, 3], [-1, 0, 0, 0, 0], 5)
+    ctx.set_update_mode(tr.TR_UPDATE_FIRST)
+    ctx.op_matrix_update(torch.from_numpy(S).cuda(), torch.from_numpy(topk).cuda())
+    M = ctx.matrix_store()
+    assert M[1].tolist() == [int(x) for x in g["expect_first 1"][0]]
+    with pytest.raises(tr.TRError):
+        ctx.set_update_mode(4)

@@ -210,3 +210,18 @@ def test_topk_equals_full_sort_with_ties():
 def test_topk_signed_zero_is_a_tie():
     p = np.array([-0.0, 0.0, -1.0, 0.0], np.float32)
     assert O.topk_ids(p, 3).tolist() == [0, 1, 3]
+
+
+def test_update_first_and_last_restricted_to_path():
+    # token 7 occurs at nodes 0, 2, 3; only nodes 0 and 3 are on the path
+    S = np.array([7, 5, 7, 7])
+    topk = np.array([[1, 1], [2, 2], [3, 3], [4, 4]])
+    M = np.zeros((9, 2), np.int64)
+    O.update_matrix(M, S, topk, "last", nodes=[0, 3])
+    assert M[7].tolist() == [4, 4] and (M[5] == 0).all()
+    M[:] = 0
+    O.update_matrix(M, S, topk, "first", nodes=[0, 3])
+    assert M[7].tolist() == [1, 1]
+    M[:] = 0
+    O.update_matrix(M, S, topk, "first")
+    assert M[7].tolist() == [1, 1] and M[5].tolist() == [2, 2]
