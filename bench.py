@@ -90,6 +90,35 @@ def cpu_baseline(sh, w_gpu, tmpl, prompt, n_steps, synth):
             "tokens_per_s": emitted / dt}
 
 
+def attention_microbench(sh, tmpl, torch, tr, L=1024, reps=5):
+    """Tree attention alone (attention kernel + split merge) at the kernel-microbenchmark shape: 32 heads of
+    128, L = 1024 committed positions, the 80-node tree, N(0,1) bf16 Q/K/V.  One launch per cache layer, so
+    consecutive launches read different 18 MB K/V blocks (32 layers = 580 MB, beyond the Infinity Cache)."""
+    n, H, hd = tmpl.n_nodes, sh.n_heads, sh.head_dim
+    kv = tr.KVDesc(sh, L + n)
+    kv.k.normal_()
+    kv.v.normal_()
+    kv.reset(L)
+    ctx = tr.Context(64, 8, tmpl.parent, tmpl.rank, tmpl.n_layers)
+    q = torch.randn(n, H, hd, device="cuda").to(torch.bfloat16)
+    o = torch.zeros_like(q)
+    ws = torch.empty(16 * 128 * H * (2 + hd) * 4 + 4096, dtype=torch.uint8, device="cuda")
+    for layer in range(sh.n_layers):
+        ctx.op_tree_attention(kv, layer, H, q, o, ws)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        for layer in range(sh.n_layers):
+            ctx.op_tree_attention(kv, layer, H, q, o, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * sh.n_layers)
+    nbytes = (L + n) * sh.n_kv_heads * hd * 2 * 2 + 2 * n * H * hd * 2    # K, V, Q, O
+    return {"workload": f"H={H} Hkv={sh.n_kv_heads} hd={hd} L={L} N={n}, bf16, {sh.n_layers} rotating cache layers",
+            "us_per_layer": us, "algorithmic_bytes_per_layer": nbytes, "achieved_GBs": nbytes / us * 1e-3,
+            "frac_of_peak_hbm": nbytes / us * 1e-3 / PEAK_HBM_GBS}
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -234,6 +263,8 @@ def main():
         torch.cuda.synchronize()
         out["calibrate_copy_bytes_each_way"] = bufs[0].numel() * 4
     del bufs
+
+    out["tree_attention"] = attention_microbench(sh, tmpl, torch, tr)
 
     if a.cpu_steps > 0:
         out["cpu_baseline"] = cpu_baseline(sh, w, tmpl, prompt, a.cpu_steps, synth)

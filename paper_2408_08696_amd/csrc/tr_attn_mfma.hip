@@ -24,6 +24,8 @@ namespace tr {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 __device__ inline f32x4 mfma16a(const u32x4 &a, const u32x4 &b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -72,7 +74,11 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
   f32x4 acc[8];
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m = NEG_BIG, lsum = 0.f;
+  // running sum l of the (bf16-rounded) probabilities, kept as the product of an all-ones A tile with
+  // P^T: every row of that product is the column sum, so each lane ends with l of its own node
+  f32x4 accl = f32x4{0.f, 0.f, 0.f, 0.f};
+  const u32x4 ones = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  float m = NEG_BIG;
   const float sc = 0.08838834764831845f * 1.4426950408889634f; // 1/sqrt(128) * log2(e)
 
   u32x4 stage[PER_THREAD];
@@ -92,6 +98,10 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
     }
   };
 
+  // The loop is bound by the vector ALU work per score, not by the K/V stream, so that work is kept
+  // minimal: tiles that lie wholly in the committed prefix skip the mask, the scale is folded into the
+  // exponent with one fma, the accumulators are rescaled only when some lane's maximum moved, and the
+  // bf16 rounding of the probabilities is the hardware's packed conversion.
   if (t0 < t1) fetch(t0);
   for (int t = t0; t < t1; ++t) {
     const int buf = (t - t0) & 1;
@@ -107,49 +117,69 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
       s0 = mfma16a(kt[c * 64 + lane], qf[c], s0);
       s1 = mfma16a(kt[(4 + c) * 64 + lane], qf[c], s1);
     }
-    float x[8];
-    bool vis[8];
-    const int pbase = t * 32 + 4 * g;
+    const bool in_prefix = t * 32 + 32 <= L; // uniform: every key of the tile is visible to every node
+    float pr[8];
+    if (in_prefix) {
+      float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])), fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m, mx * sc);
+      if (__any(m_new > m)) {
+        const float corr = __builtin_amdgcn_exp2f(m - m_new);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int p = pbase + (e >> 2) * 16 + (e & 3);
-      bool v = p < L;
-      if (!v && p < total) {
-        const int j = p - L;
-        v = j < 64 ? ((a0 >> j) & 1ull) : ((a1 >> (j - 64)) & 1ull);
+        for (int dt = 0; dt < 8; ++dt) {
+          acc[dt][0] *= corr; acc[dt][1] *= corr; acc[dt][2] *= corr; acc[dt][3] *= corr;
+        }
+        accl[0] *= corr; accl[1] *= corr; accl[2] *= corr; accl[3] *= corr;
+        m = m_new;
       }
-      vis[e] = v;
-      const float sv = (e < 4 ? s0[e & 3] : s1[e & 3]) * sc;
-      x[e] = v ? sv : NEG_BIG;
-    }
-    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m, mx);
-    const float corr = exp2f(m - m_new);
-    m = m_new;
-    float ps = 0.f;
-    uint32_t pk[4];
 #pragma unroll
-    for (int e = 0; e < 8; e += 2) {
-      const float p0 = vis[e] ? exp2f(x[e] - m_new) : 0.f;
-      const float p1 = vis[e + 1] ? exp2f(x[e + 1] - m_new) : 0.f;
-      const bf16_t b0 = f32_to_bf16(p0), b1 = f32_to_bf16(p1);
-      // the sum uses the rounded probabilities, i.e. exactly the weights that multiply V
-      ps += bf16_to_f32(b0) + bf16_to_f32(b1);
-      pk[e >> 1] = (uint32_t)b0 | ((uint32_t)b1 << 16);
-    }
-    lsum = lsum * corr + ps;
-    const u32x4 pf = u32x4{pk[0], pk[1], pk[2], pk[3]};
+      for (int e = 0; e < 4; ++e) {
+        pr[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[e], sc, -m));
+        pr[4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[e], sc, -m));
+      }
+    } else {
+      float x[8];
+      bool vis[8];
+      const int pbase = t * 32 + 4 * g;
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) {
-      f32x4 a = acc[dt];
-      a[0] *= corr; a[1] *= corr; a[2] *= corr; a[3] *= corr;
-      acc[dt] = mfma16a(vt[dt * 64 + lane], pf, a);
+      for (int e = 0; e < 8; ++e) {
+        const int p = pbase + (e >> 2) * 16 + (e & 3);
+        bool v = p < L;
+        if (!v && p < total) {
+          const int j = p - L;
+          v = j < 64 ? ((a0 >> j) & 1ull) : ((a1 >> (j - 64)) & 1ull);
+        }
+        vis[e] = v;
+        const float sv = (e < 4 ? s0[e & 3] : s1[e & 3]) * sc;
+        x[e] = v ? sv : NEG_BIG;
+      }
+      float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m, mx);
+      if (__any(m_new > m)) {
+        const float corr = __builtin_amdgcn_exp2f(m - m_new);
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          acc[dt][0] *= corr; acc[dt][1] *= corr; acc[dt][2] *= corr; acc[dt][3] *= corr;
+        }
+        accl[0] *= corr; accl[1] *= corr; accl[2] *= corr; accl[3] *= corr;
+        m = m_new;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pr[e] = vis[e] ? __builtin_amdgcn_exp2f(x[e] - m) : 0.f;
     }
+    // P^T operand: the lane's own 8 probabilities, rounded to bf16 (round to nearest even)
+    u32x4 pf;
+#pragma unroll
+    for (int e = 0; e < 8; e += 2)
+      pf[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pr[e], pr[e + 1]}, bf16x2));
+    accl = mfma16a(ones, pf, accl);
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) acc[dt] = mfma16a(vt[dt * 64 + lane], pf, acc[dt]);
   }
-  lsum += __shfl_xor(lsum, 16);
-  lsum += __shfl_xor(lsum, 32);
+  const float lsum = accl[0];
   if (node >= n) return;
 
   if (nsplit == 1) {

@@ -14,7 +14,7 @@
 // 16*nt + l%16.
 //
 // Mapping.  One workgroup owns NW consecutive out-tiles (16*NW output features) and one of `splits`
-// K-ranges; its 8 wavefronts take interleaved k-tiles of that range, keep PF k-steps of loads in flight
+// K-ranges; its GW = 8 wavefronts (4 in the NW = 8 variant) take interleaved k-tiles of that range, keep PF k-steps of loads in flight
 // in registers, and reduce through LDS in a fixed binary tree at the end.  splits > 1 writes one partial
 // result per split (summed in a fixed order by the consumer), so results are run-to-run deterministic.
 //
@@ -33,8 +33,10 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int GEMM_WAVES = 8;
 // k-steps of loads in flight per wave, bounded by the register file: accumulators take 4*NW*NT VGPRs,
 // every stage 4*(NW+NT); 256 VGPRs per wave at two waves per SIMD, about 208 of them usable here
-__host__ __device__ constexpr int gemm_pf(int nw, int nt) {
-  const int pf = (208 - 4 * nw * nt) / (4 * (nw + nt));
+__host__ __device__ constexpr int gemm_pf(int nw, int nt, int waves) {
+  // four waves per workgroup leave one wave per SIMD and 512 registers per wave: the accumulators then
+  // sit in the upper half of the unified register file and four stages of 4*(8+5) fit the lower half
+  const int pf = waves <= 4 ? 4 : (208 - 4 * nw * nt) / (4 * (nw + nt));
   return pf < 1 ? 1 : (pf > 4 ? 4 : pf);
 }
 
@@ -70,11 +72,11 @@ hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t
 // ---------------------------------------------------------------------------------------------
 // the GEMM
 // ---------------------------------------------------------------------------------------------
-template <int NT, int NW, int MODE>
-__global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(GemmArgs g) {
+template <int NT, int NW, int MODE, int GW>
+__global__ __launch_bounds__(GW * 64) void k_gemm_mfma(GemmArgs g) {
   // SWIGLU: NW = 2P; weight tiles 0..P-1 come from the gate matrix, P..2P-1 from the up matrix
   constexpr int P = MODE == GEMM_SWIGLU ? NW / 2 : NW; // distinct out-tiles per workgroup
-  constexpr int PF = gemm_pf(NW, NT);
+  constexpr int PF = gemm_pf(NW, NT, GW);
   extern __shared__ float red[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int KT = g.K / 32;
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(GemmArgs g) {
   const int kt0 = split * per;
   const int kt1 = kt0 + per < KT ? kt0 + per : KT;
   const int first = kt0 + wave;
-  const int nsteps = first < kt1 ? (kt1 - first + GEMM_WAVES - 1) / GEMM_WAVES : 0;
+  const int nsteps = first < kt1 ? (kt1 - first + GW - 1) / GW : 0;
 
   f32x4 acc[NW][NT];
 #pragma unroll
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(GemmArgs g) {
 
   u32x4 wq[PF][NW], aq[PF][NT];
   auto issue = [&](int stage, int step) {
-    const size_t kt = (size_t)(first + step * GEMM_WAVES);
+    const size_t kt = (size_t)(first + step * GW);
 #pragma unroll
     for (int u = 0; u < NW; ++u) wq[stage][u] = __builtin_nontemporal_load(wbase[u] + kt * 64);
 #pragma unroll
@@ -149,9 +151,9 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void k_gemm_mfma(GemmArgs g) {
 
   // cross-wave reduction, a fixed binary tree through LDS: in round h the upper h waves of the
   // surviving 2h publish their accumulators and the lower h add them; wave 0 ends with the sum.
-  float4 *red4 = reinterpret_cast<float4 *>(red); // [GEMM_WAVES/2][NW][NT][64]
+  float4 *red4 = reinterpret_cast<float4 *>(red); // [GW/2][NW][NT][64]
 #pragma unroll
-  for (int h = GEMM_WAVES / 2; h >= 1; h >>= 1) {
+  for (int h = GW / 2; h >= 1; h >>= 1) {
     if (wave >= h && wave < 2 * h) {
 #pragma unroll
       for (int u = 0; u < NW; ++u)
@@ -227,13 +229,15 @@ bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O) {
 void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, const int32_t *seg_tiles, int32_t n_seg, bool swiglu,
                  int32_t max_splits, int32_t *out_p, int32_t *out_splits) {
   const int NT = (n + 15) / 16, KT = K / 32;
-  static const int cand[] = {1, 2, 3, 4, 6};
+  static const int cand[] = {1, 2, 3, 4, 6, 8};
   double best = 1e30;
   int bp = 1, bs = 1;
-  for (int ci = 0; ci < 5; ++ci) {
+  for (int ci = 0; ci < 6; ++ci) {
     const int p = cand[ci];
     const int wt = swiglu ? 2 * p : p;
-    if (wt > 6 || wt * NT > 32) continue; // accumulators must fit the register file
+    // accumulators must fit the register file; 8 out-tiles only in the four-wave variant, whose
+    // accumulators live in the upper half of the unified register file (built for 4 or 5 row tiles)
+    if (wt == 8 ? (swiglu || NT < 4 || NT > 5) : (wt > 6 || wt * NT > 32)) continue;
     for (int s = 1; s <= max_splits; s *= 2) {
       if (KT / s < GEMM_WAVES) break;
       const int wgs = ((total_tiles + p - 1) / p) * s;
@@ -251,17 +255,17 @@ void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, const int32_t *seg_t
   *out_splits = bs;
 }
 
-template <int NT, int NW, int MODE>
+template <int NT, int NW, int MODE, int GW = GEMM_WAVES>
 static hipError_t launch_k(const GemmArgs &g, int p, hipStream_t st) {
-  const size_t smem = (size_t)(GEMM_WAVES / 2) * NW * NT * 64 * 16;
+  const size_t smem = (size_t)(GW / 2) * NW * NT * 64 * 16;
   if (smem > 65536) {
     static bool once = [] {
-      return hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mfma<NT, NW, MODE>),
+      return hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mfma<NT, NW, MODE, GW>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess;
     }();
     if (!once) return hipErrorInvalidValue;
   }
-  hipLaunchKernelGGL((k_gemm_mfma<NT, NW, MODE>), dim3((g.total_tiles + p - 1) / p, g.splits), dim3(GEMM_WAVES * 64),
+  hipLaunchKernelGGL((k_gemm_mfma<NT, NW, MODE, GW>), dim3((g.total_tiles + p - 1) / p, g.splits), dim3(GW * 64),
                      smem, st, g);
   return hipGetLastError();
 }
@@ -279,6 +283,9 @@ static hipError_t launch_nt(const GemmArgs &g, hipStream_t st) {
   }
   if constexpr (NT <= 5) {
     if (p == 6) return launch_k<NT, 6, GEMM_STORE>(g, p, st);
+  }
+  if constexpr (NT == 4 || NT == 5) {
+    if (p == 8) return launch_k<NT, 8, GEMM_STORE, 4>(g, p, st);
   }
   switch (p) {
   case 1: return launch_k<NT, 1, GEMM_STORE>(g, p, st);
