@@ -43,6 +43,11 @@ def parse():
     return ap.parse_args()
 
 
+def say(*a):
+    """Progress line on stderr (stdout carries only the JSON line)."""
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
 def timed_steps(eng, torch, n):
     torch.cuda.synchronize()
     l0 = int(eng.kv.d_len.item())
@@ -137,7 +142,26 @@ def main():
     sh = synth.SHAPES[a.shape]
     tmpl = synth.tree80()
     K = 8
-    w = synth.make_weights(sh, seed=0, device="cuda")
+    # a model too large to hold twice (row-major + packed) is generated and packed one layer at a time;
+    # the row-major originals are then gone, so the oracle baseline (which needs them) is skipped
+    streaming_build = sh.weight_params() * 2 * 2 > 200e9
+    if streaming_build:
+        packed = synth.head_weights(sh, seed=0, device="cuda")
+        packed["lm_head"] = tr.pack_weight(packed["lm_head"])
+        packed["layers"] = []
+        for l in range(sh.n_layers):
+            lw = synth.layer_weights(sh, l, seed=0, device="cuda")
+            packed["layers"].append({k: (tr.pack_weight(v) if k in tr.ModelDesc.MATS else v) for k, v in lw.items()})
+            del lw
+            if l % 8 == 7:
+                torch.cuda.synchronize()
+                say(f"layer {l + 1}/{sh.n_layers} generated and packed")
+        w = None
+        model = tr.ModelDesc(sh, packed, pack=True, prepacked=True)
+        del packed
+    else:
+        w = synth.make_weights(sh, seed=0, device="cuda")
+        model = None
     prompt = synth.zipf_prompt(sh.vocab, a.prompt_len, seed=0, ngram=8).tolist()
     M0 = synth.init_matrix(sh.vocab, K)
     total_steps = a.warmup + a.steps + a.profile_steps
@@ -146,7 +170,8 @@ def main():
     if a.sweep_nodes:
         # Step time versus tree size (Section 5.1 / Figure 3a asks where verifying more nodes stops being
         # as cheap as one token): same model, prompt and KV length, one engine per tree size.
-        model = tr.ModelDesc(sh, w)
+        if model is None:
+            model = tr.ModelDesc(sh, w)
         del w
         rows = []
         for nn in [int(v) for v in a.sweep_nodes.split(",")]:
@@ -170,11 +195,16 @@ def main():
                           "sweep": rows}))
         return
 
-    eng = tr.Engine(sh, w, tmpl, k=K, capacity=cap, keep_logits=False)
+    if model is None:
+        model = tr.ModelDesc(sh, w)
+    eng = tr.Engine(sh, None, tmpl, k=K, capacity=cap, keep_logits=False, model=model)
     eng.ctx.matrix_load(M0)
+    say("model ready; prefill")
     eng.prefill(prompt)
     timed_steps(eng, torch, a.warmup)
+    say("timing", a.steps, "steps")
     dt, toks = timed_steps(eng, torch, a.steps)
+    say(f"{dt / a.steps * 1e3:.3f} ms/step")
     ms_step = dt / a.steps * 1e3
     steps_s = a.steps / dt
     mat = toks / a.steps
@@ -208,7 +238,7 @@ def main():
                      "frac": wbytes / (PEAK_HBM_GBS * 1e9) * 1e3 / ms_step}
 
     out = {
-        "metric": "TR steps/s, 7B-shape bf16, 1 GPU", "value": steps_s, "unit": "steps/s", "n_gpus": 1,
+        "metric": f"TR steps/s, {sh.name.upper()}-shape bf16, 1 GPU", "value": steps_s, "unit": "steps/s", "n_gpus": 1,
         "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{sh.name}-shape random-init Llama bf16, batch 1, {tmpl.n_nodes}-node "
@@ -228,7 +258,9 @@ def main():
     del eng
 
     if not a.no_ar:
-        ar = tr.Engine(sh, w, synth.single(), k=K, capacity=a.prompt_len + a.warmup + a.steps + 64, keep_logits=False)
+        say("autoregressive comparison")
+        ar = tr.Engine(sh, None, synth.single(), k=K, capacity=a.prompt_len + a.warmup + a.steps + 64,
+                       keep_logits=False, model=model)
         ar.ctx.matrix_load(M0)
         ar.prefill(prompt)
         timed_steps(ar, torch, a.warmup)
@@ -264,9 +296,10 @@ def main():
         out["calibrate_copy_bytes_each_way"] = bufs[0].numel() * 4
     del bufs
 
+    say("attention microbenchmark, oracle baseline")
     out["tree_attention"] = attention_microbench(sh, tmpl, torch, tr)
 
-    if a.cpu_steps > 0:
+    if a.cpu_steps > 0 and w is not None:
         out["cpu_baseline"] = cpu_baseline(sh, w, tmpl, prompt, a.cpu_steps, synth)
     else:
         out["cpu_baseline"] = None

@@ -13,8 +13,8 @@
 // With A = weight tile and B = activation tile, lane l ends with outputs o0 + 4*(l/16) .. +3 of row
 // 16*nt + l%16.
 //
-// Mapping.  One workgroup owns NW consecutive out-tiles (16*NW output features) and one of `splits`
-// K-ranges; its GW = 8 wavefronts (4 in the NW = 8 variant) take interleaved k-tiles of that range, keep PF k-steps of loads in flight
+// Mapping.  One workgroup owns up to NW consecutive out-tiles (16*NW output features; the tiles are dealt
+// evenly over the workgroups) and one of `splits` K-ranges; its GW = 8 wavefronts (4 in the NW = 8 variant) take interleaved k-tiles of that range, keep PF k-steps of loads in flight
 // in registers, and reduce through LDS in a fixed binary tree at the end.  splits > 1 writes one partial
 // result per split (summed in a fixed order by the consumer), so results are run-to-run deterministic.
 //
@@ -81,14 +81,17 @@ __global__ __launch_bounds__(GW * 64) void k_gemm_mfma(GemmArgs g) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int KT = g.K / 32;
 
-  // out-tiles owned by this workgroup, numbered across the concatenated segments (weight matrices);
-  // each tile looks up its own segment, so a workgroup may straddle two matrices
-  const int tile0 = blockIdx.x * P;
-  const int n_valid = g.total_tiles - tile0 < P ? g.total_tiles - tile0 : P;
+  // out-tiles owned by this workgroup: the T tiles are dealt to the G workgroups in contiguous ranges of
+  // T/G tiles, the first T%G of them one longer (the host picks G >= T/P, so no range exceeds P).  Tiles
+  // are numbered across the concatenated segments (weight matrices) and each looks up its own segment,
+  // so a workgroup may straddle two matrices.
+  const int bx = blockIdx.x;
+  const int tile0 = bx * g.part_q + (bx < g.part_rem ? bx : g.part_rem);
+  const int n_valid = g.part_q + (bx < g.part_rem ? 1 : 0);
   const u32x4 *wbase[NW];
 #pragma unroll
   for (int u = 0; u < P; ++u) {
-    int t = tile0 + (u < n_valid ? u : 0); // tiles past the end re-read a valid tile, never stored
+    int t = tile0 + (u < n_valid ? u : 0); // unused slots re-read the first tile (a cache hit), never stored
     int sidx = 0;
     while (sidx + 1 < g.n_seg && t >= g.seg[sidx].out_tiles) {
       t -= g.seg[sidx].out_tiles;
@@ -223,40 +226,63 @@ bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O) {
   return n >= 1 && n <= TR_MAX_NODES && K % 32 == 0 && O % 32 == 0;
 }
 
-// Pick (P out-tiles per workgroup, K-splits).  Cost model in KiB moved through L2 per workgroup, times
-// the number of rounds 256 compute units need: per k-tile a workgroup reads `wt` KiB of weights and NT
-// KiB of activations; with splits > 1 every workgroup also writes (and the consumer re-reads) wt*NT KiB.
-void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, const int32_t *seg_tiles, int32_t n_seg, bool swiglu,
-                 int32_t max_splits, int32_t *out_p, int32_t *out_splits) {
+// Kernel variants: (P out-tiles per workgroup, waves).  Accumulators take 4*P*NT registers (twice that
+// for SWIGLU pairs), so the larger ones exist only for few row tiles; 8 weight tiles need the four-wave
+// form, whose accumulators live in the upper half of the unified register file.
+static bool variant_ok(int NT, int p, bool swiglu) {
+  const int wt = swiglu ? 2 * p : p;
+  if (wt == 8) return NT == 4 || NT == 5;
+  if (wt == 6) return NT <= 5;
+  if (swiglu) return wt == 2 || wt == 4;
+  return wt >= 1 && wt <= 4;
+}
+
+// Pick (P, workgroups per K-split, K-splits).  About max(ceil(T/P), min(T, 256/S)) workgroups share the T
+// out-tiles evenly.  The estimate is the slowest workgroup's time in each round of 256 workgroups: the
+// KiB it pulls through L2 (its weight tiles once, the activation block of its K-range once) at the
+// per-CU rate, or the round's weight stream at the HBM rate if that is slower, plus a fixed cost per
+// round and what the consumer pays to re-read K-split partial sums.  Rates in KiB/us, fitted to
+// measurements on MI355X.
+void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, bool swiglu, int32_t max_splits, int32_t *out_p,
+                 int32_t *out_groups, int32_t *out_splits) {
   const int NT = (n + 15) / 16, KT = K / 32;
+  const double wmul = swiglu ? 2.0 : 1.0;
   static const int cand[] = {1, 2, 3, 4, 6, 8};
   double best = 1e30;
-  int bp = 1, bs = 1;
+  int bp = swiglu ? 1 : 1, bg = total_tiles, bs = 1;
   for (int ci = 0; ci < 6; ++ci) {
     const int p = cand[ci];
-    const int wt = swiglu ? 2 * p : p;
-    // accumulators must fit the register file; 8 out-tiles only in the four-wave variant, whose
-    // accumulators live in the upper half of the unified register file (built for 4 or 5 row tiles)
-    if (wt == 8 ? (swiglu || NT < 4 || NT > 5) : (wt > 6 || wt * NT > 32)) continue;
+    if (!variant_ok(NT, p, swiglu)) continue;
     for (int s = 1; s <= max_splits; s *= 2) {
       if (KT / s < GEMM_WAVES) break;
-      const int wgs = ((total_tiles + p - 1) / p) * s;
-      const int rounds = (wgs + 255) / 256;
-      const double per_wg = (double)((KT + s - 1) / s) * (wt + NT) + (s > 1 ? 2.0 * wt * NT : 0.0) + 40.0;
-      const double cost = rounds * per_wg;
-      if (cost < best) {
-        best = cost;
+      int groups = 256 / s < total_tiles ? 256 / s : total_tiles;
+      if (groups * p < total_tiles) groups = (total_tiles + p - 1) / p;
+      const int tpw = (total_tiles + groups - 1) / groups;
+      groups = (total_tiles + tpw - 1) / tpw; // fewest workgroups with the same largest share
+      const int rounds = (groups * s + 255) / 256;
+      const double kts = (double)((KT + s - 1) / s);
+      const double l2_kib = kts * (tpw * wmul + NT);
+      const double hbm_kib = kts * tpw * wmul * (groups * s < 256 ? groups * s : 256);
+      double t = l2_kib / 48.0;
+      if (hbm_kib / 6000.0 > t) t = hbm_kib / 6000.0;
+      t = rounds * (t + 3.0) + 3.0;
+      if (s > 1) t += 2.0 * (s - 1) * NT * total_tiles / 8000.0 + 0.5; // extra KiB of partials written and re-read
+      if (t < best) {
+        best = t;
         bp = p;
+        bg = groups;
         bs = s;
       }
     }
   }
   *out_p = bp;
+  *out_groups = bg;
   *out_splits = bs;
 }
 
-template <int NT, int NW, int MODE, int GW = GEMM_WAVES>
-static hipError_t launch_k(const GemmArgs &g, int p, hipStream_t st) {
+template <int NT, int P, int MODE, int GW = GEMM_WAVES>
+static hipError_t launch_k(const GemmArgs &g, hipStream_t st) {
+  constexpr int NW = MODE == GEMM_SWIGLU ? 2 * P : P;
   const size_t smem = (size_t)(GW / 2) * NW * NT * 64 * 16;
   if (smem > 65536) {
     static bool once = [] {
@@ -265,38 +291,48 @@ static hipError_t launch_k(const GemmArgs &g, int p, hipStream_t st) {
     }();
     if (!once) return hipErrorInvalidValue;
   }
-  hipLaunchKernelGGL((k_gemm_mfma<NT, NW, MODE, GW>), dim3((g.total_tiles + p - 1) / p, g.splits), dim3(GW * 64),
-                     smem, st, g);
+  hipLaunchKernelGGL((k_gemm_mfma<NT, NW, MODE, GW>), dim3(g.groups, g.splits), dim3(GW * 64), smem, st, g);
   return hipGetLastError();
 }
 
 template <int NT>
 static hipError_t launch_nt(const GemmArgs &g, hipStream_t st) {
   const int p = g.tiles_per_wg;
-  if (g.mode == GEMM_SWIGLU) {
-    if constexpr (NT <= 5) {
-      if (p == 3) return launch_k<NT, 6, GEMM_SWIGLU>(g, p, st);
+  const bool swiglu = g.mode == GEMM_SWIGLU;
+  if (!variant_ok(NT, p, swiglu) || g.groups < 1 || g.groups > g.total_tiles ||
+      (int64_t)g.groups * p < g.total_tiles)
+    return hipErrorInvalidValue;
+  if (swiglu) {
+    if constexpr (NT == 4 || NT == 5) {
+      if (p == 4) return launch_k<NT, 4, GEMM_SWIGLU, 4>(g, st);
     }
-    if (p == 2) return launch_k<NT, 4, GEMM_SWIGLU>(g, p, st);
-    if (p == 1) return launch_k<NT, 2, GEMM_SWIGLU>(g, p, st);
+    if constexpr (NT <= 5) {
+      if (p == 3) return launch_k<NT, 3, GEMM_SWIGLU>(g, st);
+    }
+    if (p == 2) return launch_k<NT, 2, GEMM_SWIGLU>(g, st);
+    if (p == 1) return launch_k<NT, 1, GEMM_SWIGLU>(g, st);
     return hipErrorInvalidValue;
   }
-  if constexpr (NT <= 5) {
-    if (p == 6) return launch_k<NT, 6, GEMM_STORE>(g, p, st);
-  }
   if constexpr (NT == 4 || NT == 5) {
-    if (p == 8) return launch_k<NT, 8, GEMM_STORE, 4>(g, p, st);
+    if (p == 8) return launch_k<NT, 8, GEMM_STORE, 4>(g, st);
+  }
+  if constexpr (NT <= 5) {
+    if (p == 6) return launch_k<NT, 6, GEMM_STORE>(g, st);
   }
   switch (p) {
-  case 1: return launch_k<NT, 1, GEMM_STORE>(g, p, st);
-  case 2: return launch_k<NT, 2, GEMM_STORE>(g, p, st);
-  case 3: return launch_k<NT, 3, GEMM_STORE>(g, p, st);
-  case 4: return launch_k<NT, 4, GEMM_STORE>(g, p, st);
+  case 1: return launch_k<NT, 1, GEMM_STORE>(g, st);
+  case 2: return launch_k<NT, 2, GEMM_STORE>(g, st);
+  case 3: return launch_k<NT, 3, GEMM_STORE>(g, st);
+  case 4: return launch_k<NT, 4, GEMM_STORE>(g, st);
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st) {
+hipError_t launch_gemm_mfma(const GemmArgs &args, hipStream_t st) {
+  if (args.groups < 1 || args.total_tiles < 1) return hipErrorInvalidValue;
+  GemmArgs g = args;
+  g.part_q = g.total_tiles / g.groups;
+  g.part_rem = g.total_tiles % g.groups;
   switch ((g.n + 15) / 16) {
   case 1: return launch_nt<1>(g, st);
   case 2: return launch_nt<2>(g, st);

@@ -39,21 +39,20 @@ struct GemmArgs {
   int32_t n_ssq, norm_dim;
   float eps;
   int32_t total_tiles;  // sum of seg[i].out_tiles
-  int32_t tiles_per_wg; // P, from gemm_choose
+  int32_t tiles_per_wg; // most out-tiles (SWIGLU: gate/up tile pairs) a workgroup handles per pass
+  int32_t groups;       // workgroups per K-split; each owns a contiguous ~total_tiles/groups out-tiles
+  int32_t part_q, part_rem; // total_tiles / groups and total_tiles % groups (filled by launch_gemm_mfma)
 };
 
-// Fills g.total_tiles, g.tiles_per_wg and g.splits (<= max_splits; 1 for GEMM_SWIGLU).
-void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, const int32_t *seg_tiles, int32_t n_seg, bool swiglu,
-                 int32_t max_splits, int32_t *out_p, int32_t *out_splits);
+// Fills g.total_tiles, g.tiles_per_wg, g.groups and g.splits (<= max_splits; 1 for GEMM_SWIGLU).
+void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, bool swiglu, int32_t max_splits, int32_t *out_pmax,
+                 int32_t *out_groups, int32_t *out_splits);
 inline void gemm_plan(GemmArgs &g, int32_t max_splits) {
-  int32_t st[3] = {0, 0, 0}, total = 0;
-  for (int i = 0; i < g.n_seg; ++i) {
-    st[i] = g.seg[i].out_tiles;
-    total += st[i];
-  }
+  int32_t total = 0;
+  for (int i = 0; i < g.n_seg; ++i) total += g.seg[i].out_tiles;
   g.total_tiles = total;
-  gemm_choose(g.n, g.K, total, st, g.n_seg, g.mode == GEMM_SWIGLU, g.mode == GEMM_SWIGLU ? 1 : max_splits,
-              &g.tiles_per_wg, &g.splits);
+  gemm_choose(g.n, g.K, total, g.mode == GEMM_SWIGLU, g.mode == GEMM_SWIGLU ? 1 : max_splits, &g.tiles_per_wg,
+              &g.groups, &g.splits);
 }
 
 bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O);

@@ -106,6 +106,36 @@ def uniform_tensor(shape: Sequence[int], scale: float, seed: int, tensor_id: int
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 
+def head_weights(shape: ModelShape, seed: int = 0, device: str | torch.device = "cpu") -> dict:
+    """Embedding table, final norm gain and LM head of make_weights (same values)."""
+    dt = _TORCH_DTYPE[shape.dtype]
+    d = shape.d_model
+    return {
+        "embed": uniform_tensor((shape.vocab, d), float(np.sqrt(3.0)), seed, 1, dt, device),
+        "final_norm": torch.ones(d, dtype=dt, device=device),
+        "lm_head": uniform_tensor((shape.vocab, d), float(np.sqrt(3.0 / d)), seed, 2, dt, device),
+    }
+
+
+def layer_weights(shape: ModelShape, l: int, seed: int = 0, device: str | torch.device = "cpu") -> dict:
+    """Layer l of make_weights (same values), so that a large model can be built one layer at a time."""
+    dt = _TORCH_DTYPE[shape.dtype]
+    d, hd = shape.d_model, shape.head_dim
+    hq, hk, f = shape.n_heads * hd, shape.n_kv_heads * hd, shape.d_ffn
+
+    def mat(out_f: int, in_f: int, tid: int) -> torch.Tensor:
+        return uniform_tensor((out_f, in_f), float(np.sqrt(3.0 / in_f)), seed, tid, dt, device)
+
+    base = 16 * (l + 1)
+    return {
+        "attn_norm": torch.ones(d, dtype=dt, device=device),
+        "wq": mat(hq, d, base + 0), "wk": mat(hk, d, base + 1), "wv": mat(hk, d, base + 2),
+        "wo": mat(d, hq, base + 3),
+        "ffn_norm": torch.ones(d, dtype=dt, device=device),
+        "w_gate": mat(f, d, base + 4), "w_up": mat(f, d, base + 5), "w_down": mat(d, f, base + 6),
+    }
+
+
 def make_weights(shape: ModelShape, seed: int = 0, device: str | torch.device = "cpu") -> dict:
     """Random-init Llama-style weights, all matrices stored [out, in] row-major.
 
@@ -114,28 +144,8 @@ def make_weights(shape: ModelShape, seed: int = 0, device: str | torch.device = 
     {"embed", "final_norm", "lm_head", "layers": [{"attn_norm","wq","wk","wv","wo",
     "ffn_norm","w_gate","w_up","w_down"}, ...]} as torch tensors on `device`.
     """
-    dt = _TORCH_DTYPE[shape.dtype]
-    d, hd = shape.d_model, shape.head_dim
-    hq, hk, f = shape.n_heads * hd, shape.n_kv_heads * hd, shape.d_ffn
-
-    def mat(out_f: int, in_f: int, tid: int) -> torch.Tensor:
-        return uniform_tensor((out_f, in_f), float(np.sqrt(3.0 / in_f)), seed, tid, dt, device)
-
-    w = {
-        "embed": uniform_tensor((shape.vocab, d), float(np.sqrt(3.0)), seed, 1, dt, device),
-        "final_norm": torch.ones(d, dtype=dt, device=device),
-        "lm_head": mat(shape.vocab, d, 2),
-        "layers": [],
-    }
-    for l in range(shape.n_layers):
-        base = 16 * (l + 1)
-        w["layers"].append({
-            "attn_norm": torch.ones(d, dtype=dt, device=device),
-            "wq": mat(hq, d, base + 0), "wk": mat(hk, d, base + 1), "wv": mat(hk, d, base + 2),
-            "wo": mat(d, hq, base + 3),
-            "ffn_norm": torch.ones(d, dtype=dt, device=device),
-            "w_gate": mat(f, d, base + 4), "w_up": mat(f, d, base + 5), "w_down": mat(d, f, base + 6),
-        })
+    w = head_weights(shape, seed, device)
+    w["layers"] = [layer_weights(shape, l, seed, device) for l in range(shape.n_layers)]
     return w
 
 

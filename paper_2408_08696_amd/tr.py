@@ -246,15 +246,16 @@ class ModelDesc:
     """tr_model over torch tensors (kept alive here).  `weights` has the layout of
     synth.make_weights; `shape` carries the dimensions.  With pack=True (default where the shape
     allows it) every projection matrix and the LM head are repacked once into the MFMA operand
-    order; the row-major originals are not referenced afterwards."""
+    order; the row-major originals are not referenced afterwards.  prepacked=True says the caller
+    has already done that with pack_weight (a model too large to hold twice is packed layer by layer)."""
 
     MATS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
 
-    def __init__(self, shape, weights: dict, pack: Optional[bool] = None):
+    def __init__(self, shape, weights: dict, pack: Optional[bool] = None, prepacked: bool = False):
         if pack is None:
             pack = can_pack(shape)
         self.packed = bool(pack)
-        if pack:
+        if pack and not prepacked:
             weights = {"embed": weights["embed"], "final_norm": weights["final_norm"],
                        "lm_head": pack_weight(weights["lm_head"]),
                        "layers": [{k: (pack_weight(v) if k in self.MATS else v) for k, v in lw.items()}
