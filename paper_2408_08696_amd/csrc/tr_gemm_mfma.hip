@@ -15,7 +15,8 @@
 //
 // Mapping.  One workgroup owns up to NW consecutive out-tiles (16*NW output features; the tiles are dealt
 // evenly over the workgroups) and one of `splits` K-ranges; its GW = 8 wavefronts (4 in the NW = 8 variant) take interleaved k-tiles of that range, keep PF k-steps of loads in flight
-// in registers, and reduce through LDS in a fixed binary tree at the end.  splits > 1 writes one partial
+// in registers, and reduce through LDS at the end, each wave ending up with (and storing) its share of
+// the output tiles.  splits > 1 writes one partial
 // result per split (summed in a fixed order by the consumer), so results are run-to-run deterministic.
 //
 // Why NW is large.  Every workgroup reads the whole activation block of its K-range from L2 (16*NT rows),
@@ -152,72 +153,93 @@ __global__ __launch_bounds__(GW * 64) void k_gemm_mfma(GemmArgs g) {
     }
   }
 
-  // cross-wave reduction, a fixed binary tree through LDS: in round h the upper h waves of the
-  // surviving 2h publish their accumulators and the lower h add them; wave 0 ends with the sum.
-  float4 *red4 = reinterpret_cast<float4 *>(red); // [GW/2][NW][NT][64]
+  // Cross-wave reduction as a reduce-scatter through LDS, then a distributed epilogue.  The NW*NT
+  // accumulator tiles form U units of TPU tiles (one tile; for SWIGLU a gate tile and its up tile); wave w
+  // owns units w*UPW .. w*UPW+UPW-1.  In each of two passes (LDS holds half of all partial tiles) every
+  // wave publishes its partial of the tiles owned by that pass's waves, and each owner adds the GW
+  // partials of its tiles in wave order (a fixed order: results are run-to-run identical).  Every wave
+  // then scales, activates and stores its own few tiles, instead of one wave storing them all.
+  constexpr int TPU = MODE == GEMM_SWIGLU ? 2 : 1;
+  constexpr int U = P * NT;
+  constexpr int UPW = (U + GW - 1) / GW;
+  constexpr int OWN0 = GW / 2; // waves 0 .. OWN0-1 own the units of pass 0
+  float4 *red4 = reinterpret_cast<float4 *>(red); // [unit slot * TPU + k][GW][64]
+  float *sc_lds = red + (size_t)OWN0 * UPW * TPU * GW * 64 * 4; // [NT * 16] per-row scale
+  if (wave == 0) {
 #pragma unroll
-  for (int h = GW / 2; h >= 1; h >>= 1) {
-    if (wave >= h && wave < 2 * h) {
-#pragma unroll
-      for (int u = 0; u < NW; ++u)
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-          red4[(((wave - h) * NW + u) * NT + t) * 64 + lane] =
-              float4{acc[u][t][0], acc[u][t][1], acc[u][t][2], acc[u][t][3]};
-    }
-    __syncthreads();
-    if (wave < h) {
-#pragma unroll
-      for (int u = 0; u < NW; ++u)
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const float4 o = red4[((wave * NW + u) * NT + t) * 64 + lane];
-          acc[u][t][0] += o.x; acc[u][t][1] += o.y; acc[u][t][2] += o.z; acc[u][t][3] += o.w;
-        }
-    }
-    __syncthreads();
-  }
-  if (wave != 0) return;
-  const int r = lane & 15, gq = lane >> 4;
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int row = 16 * t + r;
-    if (g.row_ssq != nullptr) {
+    for (int t = 0; t < NT; ++t) {
       float ss = row_ss[t][0] + row_ss[t][1];
       ss += __shfl_xor(ss, 16);
       ss += __shfl_xor(ss, 32);
-      const float sc = 1.0f / sqrtf(ss / (float)g.norm_dim + g.eps);
+      if (lane < 16) sc_lds[16 * t + lane] = g.row_ssq != nullptr ? 1.0f / sqrtf(ss / (float)g.norm_dim + g.eps) : 1.0f;
+    }
+  }
+  f32x4 fin[UPW][TPU];
 #pragma unroll
-      for (int u = 0; u < NW; ++u) {
-        acc[u][t][0] *= sc; acc[u][t][1] *= sc; acc[u][t][2] *= sc; acc[u][t][3] *= sc;
+  for (int pass = 0; pass < 2; ++pass) {
+    if (pass == 1 && OWN0 * UPW >= U) break; // every unit was owned by a pass-0 wave
+#pragma unroll
+    for (int u = 0; u < P; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const int id = u * NT + t;
+        if ((id / UPW >= OWN0) != (pass == 1)) continue;
+        const int slot = (id - pass * OWN0 * UPW) * TPU;
+        red4[((size_t)slot * GW + wave) * 64 + lane] = float4{acc[u][t][0], acc[u][t][1], acc[u][t][2], acc[u][t][3]};
+        if (MODE == GEMM_SWIGLU)
+          red4[((size_t)(slot + 1) * GW + wave) * 64 + lane] =
+              float4{acc[P + u][t][0], acc[P + u][t][1], acc[P + u][t][2], acc[P + u][t][3]};
+      }
+    __syncthreads();
+    if ((wave >= OWN0) == (pass == 1)) {
+#pragma unroll
+      for (int i = 0; i < UPW; ++i) {
+        const int id = wave * UPW + i;
+#pragma unroll
+        for (int k = 0; k < TPU; ++k) {
+          f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (id < U) {
+            const float4 *src = red4 + ((size_t)((id - pass * OWN0 * UPW) * TPU + k) * GW) * 64 + lane;
+#pragma unroll
+            for (int w = 0; w < GW; ++w) {
+              const float4 o = src[w * 64];
+              sum[0] += o.x; sum[1] += o.y; sum[2] += o.z; sum[3] += o.w;
+            }
+          }
+          fin[i][k] = sum;
+        }
       }
     }
+    if (pass == 0 && OWN0 * UPW < U) __syncthreads(); // pass 1 reuses the buffer
+  }
+
+  const int r = lane & 15, gq = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < UPW; ++i) {
+    const int id = wave * UPW + i;
+    if (id >= U) continue;
+    const int u = id / NT, t = id - u * NT;
+    if (u >= n_valid) continue;
+    const int row = 16 * t + r;
+    const float sc = sc_lds[row];
+    const int o = (tile0 + u) * 16 + 4 * gq;
     if (MODE == GEMM_STORE) {
       if (row >= g.n) continue;
       float *yb = g.y + (size_t)split * g.split_stride + (size_t)row * g.ldy;
-#pragma unroll
-      for (int u = 0; u < P; ++u) {
-        if (u >= n_valid) continue;
-        const int o = (tile0 + u) * 16 + 4 * gq;
-        *reinterpret_cast<float4 *>(yb + o) = float4{acc[u][t][0], acc[u][t][1], acc[u][t][2], acc[u][t][3]};
-      }
+      *reinterpret_cast<float4 *>(yb + o) = float4{fin[i][0][0] * sc, fin[i][0][1] * sc, fin[i][0][2] * sc, fin[i][0][3] * sc};
     } else {
       // h[row, o .. o+3] = bf16(silu(gate) * up), written in fragment order over (k = o, NT row tiles);
       // rows past n are written as zeros so the consumer's operand tiles are fully defined
       const bool live = row < g.n;
-#pragma unroll
-      for (int u = 0; u < P; ++u) {
-        if (u >= n_valid) continue;
-        const f32x4 gt = acc[u][t], up = acc[MODE == GEMM_SWIGLU ? P + u : u][t];
-        ushort4 hv;
-        hv.x = live ? f32_to_bf16(gt[0] / (1.0f + __expf(-gt[0])) * up[0]) : (bf16_t)0;
-        hv.y = live ? f32_to_bf16(gt[1] / (1.0f + __expf(-gt[1])) * up[1]) : (bf16_t)0;
-        hv.z = live ? f32_to_bf16(gt[2] / (1.0f + __expf(-gt[2])) * up[2]) : (bf16_t)0;
-        hv.w = live ? f32_to_bf16(gt[3] / (1.0f + __expf(-gt[3])) * up[3]) : (bf16_t)0;
-        const int o = (tile0 + u) * 16 + 4 * gq; // k index of the consumer
-        const size_t slot = ((size_t)(o >> 5) * NT + t) * 64 + r + 16 * ((o & 31) >> 3);
-        *reinterpret_cast<ushort4 *>(g.h_frag + slot * 8 + (o & 7)) = hv;
-      }
+      const f32x4 gt = f32x4{fin[i][0][0] * sc, fin[i][0][1] * sc, fin[i][0][2] * sc, fin[i][0][3] * sc};
+      const f32x4 up = f32x4{fin[i][TPU - 1][0] * sc, fin[i][TPU - 1][1] * sc, fin[i][TPU - 1][2] * sc, fin[i][TPU - 1][3] * sc};
+      ushort4 hv;
+      hv.x = live ? f32_to_bf16(gt[0] / (1.0f + __expf(-gt[0])) * up[0]) : (bf16_t)0;
+      hv.y = live ? f32_to_bf16(gt[1] / (1.0f + __expf(-gt[1])) * up[1]) : (bf16_t)0;
+      hv.z = live ? f32_to_bf16(gt[2] / (1.0f + __expf(-gt[2])) * up[2]) : (bf16_t)0;
+      hv.w = live ? f32_to_bf16(gt[3] / (1.0f + __expf(-gt[3])) * up[3]) : (bf16_t)0;
+      const size_t slot = ((size_t)(o >> 5) * NT + t) * 64 + r + 16 * ((o & 31) >> 3);
+      *reinterpret_cast<ushort4 *>(g.h_frag + slot * 8 + (o & 7)) = hv;
     }
   }
 }
@@ -283,7 +305,9 @@ void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, bool swiglu, int32_t
 template <int NT, int P, int MODE, int GW = GEMM_WAVES>
 static hipError_t launch_k(const GemmArgs &g, hipStream_t st) {
   constexpr int NW = MODE == GEMM_SWIGLU ? 2 * P : P;
-  const size_t smem = (size_t)(GW / 2) * NW * NT * 64 * 16;
+  // partial tiles of the units owned by half of the waves, from all waves, plus the per-row scales
+  constexpr int TPU = MODE == GEMM_SWIGLU ? 2 : 1, UPW = (P * NT + GW - 1) / GW;
+  const size_t smem = (size_t)(GW / 2) * UPW * TPU * GW * 64 * 16 + NT * 16 * sizeof(float);
   if (smem > 65536) {
     static bool once = [] {
       return hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mfma<NT, NW, MODE, GW>),
