@@ -151,7 +151,7 @@ def main():
         packed["layers"] = []
         for l in range(sh.n_layers):
             lw = synth.layer_weights(sh, l, seed=0, device="cuda")
-            packed["layers"].append({k: (tr.pack_weight(v) if k in tr.ModelDesc.MATS else v) for k, v in lw.items()})
+            packed["layers"].append(tr.pack_layer(sh, lw))
             del lw
             if l % 8 == 7:
                 torch.cuda.synchronize()

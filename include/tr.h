@@ -57,8 +57,13 @@ typedef enum { TR_F32 = 0, TR_BF16 = 1 } tr_dtype;
  *                  tr_pack_weight): the matrix is cut into tiles of 16 out-features x 32
  *                  in-features, tile (o/16, i/32) stored at ((o/16) * (in/32) + i/32) KiB, and inside
  *                  a tile element (o, i) sits at 16-byte slot (o%16) + 16*((i%32)/8), element i%8.
- *                  Needs out_features % 32 == 0 and in_features % 32 == 0.  This is the fast path;
- *                  row-major models run through slower shape-generic kernels.
+ *                  Needs out_features % 32 == 0 and in_features % 32 == 0.  The query and key
+ *                  projections (wq, wk) are packed by tr_pack_weight_rope instead: their rows are
+ *                  first interleaved per head so that the two features a rotary embedding rotates
+ *                  together become neighbours.  Queries and cached keys of such a model carry the
+ *                  interleaved feature order (the attention dot product is indifferent to it); cached
+ *                  values are in natural order.  This is the fast path; row-major models run through
+ *                  slower shape-generic kernels.
  * The embedding table and the norm gains are always plain arrays.
  */
 typedef enum { TR_ROW_MAJOR = 0, TR_PACKED = 1 } tr_layout;
@@ -182,6 +187,16 @@ tr_status tr_build_tree(tr_ctx *ctx, const int32_t *d_root, int32_t *d_S, void *
  * must not overlap), on the stream.  Errors: TR_EINVAL (NULL, sizes not multiples of 32).
  */
 tr_status tr_pack_weight(const void *d_src, void *d_dst, int32_t out_f, int32_t in_f, void *stream);
+
+/*
+ * The same for a query or key projection (Section 2.2: the verification forward is a Llama-style
+ * decoder whose attention uses rotary position embedding with half-split pairing): packed row
+ * h*head_dim + 2j + b takes source row h*head_dim + j + b*head_dim/2 (b = 0, 1), so that the projection
+ * kernel can rotate a pair inside one lane and write queries and keys straight from its epilogue.
+ * Errors as tr_pack_weight, plus TR_EINVAL if head_dim is not a positive multiple of 4 dividing out_f.
+ */
+tr_status tr_pack_weight_rope(const void *d_src, void *d_dst, int32_t out_f, int32_t in_f,
+                              int32_t head_dim, void *stream);
 
 /* Bytes of [device] workspace tr_verify_forward / tr_prefill need for this model (256-aligned). */
 tr_status tr_workspace_bytes(const tr_ctx *ctx, const tr_model *model, size_t *bytes);

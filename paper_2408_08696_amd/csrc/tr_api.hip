@@ -311,7 +311,18 @@ tr_status tr_op_linear(tr_ctx *c, const void *d_x, const void *d_w, int32_t dtyp
 tr_status tr_pack_weight(const void *d_src, void *d_dst, int32_t out_f, int32_t in_f, void *stream) {
   if (d_src == nullptr || d_dst == nullptr || d_src == d_dst) return TR_EINVAL;
   if (out_f <= 0 || in_f <= 0 || out_f % 32 != 0 || in_f % 32 != 0) return TR_EINVAL;
-  return launch_pack_weight((const bf16_t *)d_src, (bf16_t *)d_dst, out_f, in_f, as_stream(stream)) == hipSuccess
+  return launch_pack_weight((const bf16_t *)d_src, (bf16_t *)d_dst, out_f, in_f, 0, as_stream(stream)) == hipSuccess
+             ? TR_OK
+             : TR_EHIP;
+}
+
+tr_status tr_pack_weight_rope(const void *d_src, void *d_dst, int32_t out_f, int32_t in_f, int32_t head_dim,
+                              void *stream) {
+  if (d_src == nullptr || d_dst == nullptr || d_src == d_dst) return TR_EINVAL;
+  if (out_f <= 0 || in_f <= 0 || out_f % 32 != 0 || in_f % 32 != 0) return TR_EINVAL;
+  if (head_dim <= 0 || head_dim % 4 != 0 || out_f % head_dim != 0) return TR_EINVAL;
+  return launch_pack_weight((const bf16_t *)d_src, (bf16_t *)d_dst, out_f, in_f, head_dim, as_stream(stream)) ==
+                 hipSuccess
              ? TR_OK
              : TR_EHIP;
 }

@@ -481,7 +481,6 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
   const int NT = (n + 15) / 16;
   float *x = (float *)(ws + w.x);
   T *xn = (T *)(ws + w.xn);
-  float *qkv = (float *)(ws + w.qkv);
   T *q = (T *)(ws + w.q);
   T *attn = (T *)(ws + w.attn);
   T *hbuf = (T *)(ws + w.h);
@@ -500,7 +499,6 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
     TR_TRY(hipGetLastError());
   }
   int pending = 0; // partial sums waiting in ypart
-  int qkv_parts = 1;
   for (int l = 0; l < m.n_layers; ++l) {
     const tr_layer &lw = m.layers[l];
     {
@@ -516,18 +514,14 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
       g.seg[0] = GemmSeg{(const T *)lw.wq, hq / 16};
       g.seg[1] = GemmSeg{(const T *)lw.wk, hk / 16};
       g.seg[2] = GemmSeg{(const T *)lw.wv, hk / 16};
-      g.n_seg = 3; g.y = qkv; g.ldy = wq; g.split_stride = qstride; g.mode = GEMM_STORE;
+      g.n_seg = 3; g.mode = GEMM_STORE;
       g.row_ssq = ssq; g.n_ssq = nch; g.norm_dim = d; g.eps = m.rms_eps;
-      gemm_plan(g, GEMM_MAX_SPLITS);
-      qkv_parts = g.splits;
+      // RoPE and the query / cache writes happen in the projection's epilogue (one K-split: the epilogue
+      // needs complete sums); wq and wk are packed with interleaved rows for that
+      g.rope = GemmRope{q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, rope, kv.d_len,
+                        H, Hkv, hd, kv.capacity, kv.layout};
+      gemm_plan(g, 1);
       TR_TRY(launch_gemm_mfma(g, st));
-    }
-    {
-      ProfScope ps(prof, PC_ROPE, st);
-      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, (H + 2 * Hkv + ROPE_HPB - 1) / ROPE_HPB), dim3(256), 0, st, qkv, qkv_parts, qstride, rope, H, Hkv,
-                         hd, kv.capacity, kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz,
-                         kv.layout);
-      TR_TRY(hipGetLastError());
     }
     {
       ProfScope ps(prof, PC_ATTN, st);

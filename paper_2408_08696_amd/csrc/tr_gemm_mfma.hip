@@ -49,7 +49,7 @@ __device__ inline f32x4 mfma16(const u32x4 &a, const u32x4 &b, f32x4 c) {
 // one-time repack of a row-major [O, K] bf16 matrix into fragment order
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_pack_weight(const bf16_t *__restrict__ src, int32_t O, int32_t K,
-                                                     uint4 *__restrict__ dst) {
+                                                     int32_t rope_hd, uint4 *__restrict__ dst) {
   const int KT = K / 32;
   const size_t slot = (size_t)blockIdx.x * 256 + threadIdx.x; // one 16-byte lane slot
   const size_t total = (size_t)(O / 16) * KT * 64;
@@ -58,14 +58,18 @@ __global__ __launch_bounds__(256) void k_pack_weight(const bf16_t *__restrict__ 
   const size_t tile = slot >> 6;
   const int kt = (int)(tile % KT);
   const int ot = (int)(tile / KT);
-  const int row = ot * 16 + (lane & 15);
+  int row = ot * 16 + (lane & 15);
+  if (rope_hd > 0) { // packed row h*hd + 2j + b <- source row h*hd + j + b*hd/2
+    const int i = row % rope_hd;
+    row = row - i + (i >> 1) + (i & 1) * (rope_hd / 2);
+  }
   const int k = kt * 32 + 8 * (lane >> 4);
   dst[slot] = *reinterpret_cast<const uint4 *>(src + (size_t)row * K + k);
 }
 
-hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t K, hipStream_t st) {
+hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t K, int32_t rope_hd, hipStream_t st) {
   const size_t total = (size_t)(O / 16) * (K / 32) * 64;
-  hipLaunchKernelGGL(k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, src, O, K,
+  hipLaunchKernelGGL(k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, src, O, K, rope_hd,
                      reinterpret_cast<uint4 *>(dst));
   return hipGetLastError();
 }
@@ -225,8 +229,41 @@ __global__ __launch_bounds__(GW * 64) void k_gemm_mfma(GemmArgs g) {
     const int o = (tile0 + u) * 16 + 4 * gq;
     if (MODE == GEMM_STORE) {
       if (row >= g.n) continue;
-      float *yb = g.y + (size_t)split * g.split_stride + (size_t)row * g.ldy;
-      *reinterpret_cast<float4 *>(yb + o) = float4{fin[i][0][0] * sc, fin[i][0][1] * sc, fin[i][0][2] * sc, fin[i][0][3] * sc};
+      const f32x4 v = f32x4{fin[i][0][0] * sc, fin[i][0][1] * sc, fin[i][0][2] * sc, fin[i][0][3] * sc};
+      if (g.rope.q == nullptr) {
+        float *yb = g.y + (size_t)split * g.split_stride + (size_t)row * g.ldy;
+        *reinterpret_cast<float4 *>(yb + o) = float4{v[0], v[1], v[2], v[3]};
+      } else {
+        // fused Q/K/V epilogue: features o .. o+3 of the concatenated [q | k | v] outputs, in the
+        // interleaved order of the packed wq / wk rows: (o, o+1) and (o+2, o+3) are rotation pairs
+        const GemmRope &rp = g.rope;
+        const int hd = rp.hd, head = o / hd, dd = o - head * hd;
+        const int pos = *rp.d_len + row;
+        float a0 = v[0], b0 = v[1], a1 = v[2], b1 = v[3];
+        if (head < rp.H + rp.Hkv) {
+          const float *cs = rp.rope + (size_t)row * hd + (dd >> 1);
+          const float c0 = cs[0], c1 = cs[1], s0 = cs[hd / 2], s1 = cs[hd / 2 + 1];
+          a0 = v[0] * c0 - v[1] * s0; b0 = v[1] * c0 + v[0] * s0;
+          a1 = v[2] * c1 - v[3] * s1; b1 = v[3] * c1 + v[2] * s1;
+        }
+        const bf16_t e0 = f32_to_bf16(a0), e1 = f32_to_bf16(b0), e2 = f32_to_bf16(a1), e3 = f32_to_bf16(b1);
+        if (head < rp.H + rp.Hkv) {
+          bf16_t *dst;
+          if (head < rp.H) dst = rp.q + ((size_t)row * rp.H + head) * hd + dd;
+          else if (rp.tiled) dst = rp.k_layer + (size_t)(head - rp.H) * rp.cap * hd + kv_k_index(pos, dd);
+          else dst = rp.k_layer + ((size_t)(head - rp.H) * rp.cap + pos) * hd + dd;
+          *reinterpret_cast<ushort4 *>(dst) = ushort4{e0, e1, e2, e3};
+        } else {
+          bf16_t *dst = rp.v_layer + (size_t)(head - rp.H - rp.Hkv) * hd * rp.cap;
+          if (rp.tiled) {
+            dst[kv_v_index(pos, dd)] = e0; dst[kv_v_index(pos, dd + 1)] = e1;
+            dst[kv_v_index(pos, dd + 2)] = e2; dst[kv_v_index(pos, dd + 3)] = e3;
+          } else {
+            dst[(size_t)dd * rp.cap + pos] = e0; dst[(size_t)(dd + 1) * rp.cap + pos] = e1;
+            dst[(size_t)(dd + 2) * rp.cap + pos] = e2; dst[(size_t)(dd + 3) * rp.cap + pos] = e3;
+          }
+        }
+      }
     } else {
       // h[row, o .. o+3] = bf16(silu(gate) * up), written in fragment order over (k = o, NT row tiles);
       // rows past n are written as zeros so the consumer's operand tiles are fully defined

@@ -18,6 +18,20 @@ struct GemmSeg {
   int32_t out_tiles; // its out_features / 16
 };
 
+// Optional epilogue of the fused Q/K/V projection (GEMM_STORE, splits == 1, q != nullptr): instead of
+// storing y, rotate the query and key features (RoPE) and write queries, keys and values where the
+// attention kernel reads them.  Needs wq and wk packed with their rows interleaved per head (feature i and
+// i + head_dim/2 adjacent, see launch_pack_weight), so that a rotation pair sits in one lane; queries and
+// cached keys then carry that feature order, which the attention dot product does not care about.
+struct GemmRope {
+  bf16_t *q;             // [n, H, hd] rotated queries; nullptr switches the epilogue off
+  bf16_t *k_layer;       // this layer's K block of the cache
+  bf16_t *v_layer;       // this layer's V block of the cache
+  const float *rope;     // [rows, hd]: cos[hd/2] | sin[hd/2] of every row's position
+  const int32_t *d_len;  // committed length L; row r is written at cache position L + r
+  int32_t H, Hkv, hd, cap, tiled;
+};
+
 // y[n, O] = a[n, K] * W^T over the concatenation of up to three weight matrices (out-feature axis).
 //   GEMM_STORE : y[split][row * ldy + o] = partial sum of that K-split (float32, row-major)
 //   GEMM_SWIGLU: h_frag = bf16(silu(a W_gate^T) * (a W_up^T)) in fragment order over (k = o);
@@ -42,6 +56,7 @@ struct GemmArgs {
   int32_t tiles_per_wg; // most out-tiles (SWIGLU: gate/up tile pairs) a workgroup handles per pass
   int32_t groups;       // workgroups per K-split; each owns a contiguous ~total_tiles/groups out-tiles
   int32_t part_q, part_rem; // total_tiles / groups and total_tiles % groups (filled by launch_gemm_mfma)
+  GemmRope rope;            // Q/K/V epilogue (see above), off when rope.q == nullptr
 };
 
 // Fills g.total_tiles, g.tiles_per_wg, g.groups and g.splits (<= max_splits; 1 for GEMM_SWIGLU).
@@ -57,7 +72,9 @@ inline void gemm_plan(GemmArgs &g, int32_t max_splits) {
 
 bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O);
 hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st);
-hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t K, hipStream_t st);
+// rope_hd > 0: packed row h*rope_hd + 2j + b takes source row h*rope_hd + j + b*rope_hd/2 (query / key
+// matrices: the two features of a rotation pair become neighbours)
+hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t K, int32_t rope_hd, hipStream_t st);
 
 // Tree attention for head_dim 128, bf16 K/V/Q, split over the key axis with a merge pass.
 // len_bound: host upper bound of L + n (sizes the split count only).

@@ -81,6 +81,7 @@ _SIGS = {
     "tr_op_linear": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                      C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
     "tr_pack_weight": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
+    "tr_pack_weight_rope": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p],
     "tr_op_stream": [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
     "tr_profile_enable": [C.c_void_p, C.c_int32],
     "tr_profile_read": [C.c_void_p, C.POINTER(ProfileEntry), C.c_int32, C.POINTER(C.c_int32)],
@@ -228,13 +229,25 @@ def op_stream(src, dst=None) -> None:
     _check(lib().tr_op_stream(src.data_ptr(), _ptr(dst), src.numel() * src.element_size(), _stream()), "tr_op_stream")
 
 
-def pack_weight(w):
-    """Packed copy of a row-major bf16 [out_f, in_f] device tensor (same shape tag, packed bytes)."""
+def pack_weight(w, rope_head_dim: int = 0):
+    """Packed copy of a row-major bf16 [out_f, in_f] device tensor (same shape tag, packed bytes).
+    rope_head_dim > 0: a query / key projection, packed with its rows interleaved per head."""
     import torch
     assert w.dtype == torch.bfloat16 and w.is_contiguous() and w.dim() == 2
     out = torch.empty_like(w)
-    _check(lib().tr_pack_weight(w.data_ptr(), out.data_ptr(), w.shape[0], w.shape[1], _stream()), "tr_pack_weight")
+    if rope_head_dim > 0:
+        _check(lib().tr_pack_weight_rope(w.data_ptr(), out.data_ptr(), w.shape[0], w.shape[1], rope_head_dim,
+                                         _stream()), "tr_pack_weight_rope")
+    else:
+        _check(lib().tr_pack_weight(w.data_ptr(), out.data_ptr(), w.shape[0], w.shape[1], _stream()),
+               "tr_pack_weight")
     return out
+
+
+def pack_layer(shape, lw: dict) -> dict:
+    """One layer of synth.make_weights with every projection matrix packed (wq, wk interleaved for RoPE)."""
+    return {k: (pack_weight(v, shape.head_dim if k in ("wq", "wk") else 0) if k in ModelDesc.MATS else v)
+            for k, v in lw.items()}
 
 
 def can_pack(shape) -> bool:
@@ -258,8 +271,7 @@ class ModelDesc:
         if pack and not prepacked:
             weights = {"embed": weights["embed"], "final_norm": weights["final_norm"],
                        "lm_head": pack_weight(weights["lm_head"]),
-                       "layers": [{k: (pack_weight(v) if k in self.MATS else v) for k, v in lw.items()}
-                                  for lw in weights["layers"]]}
+                       "layers": [pack_layer(shape, lw) for lw in weights["layers"]]}
         self.weights = weights
         n = shape.n_layers
         self._layers = (Layer * n)()

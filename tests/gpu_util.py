@@ -95,16 +95,22 @@ def kv_maps(cap, hd=128):
     return _k_index(p, d), _v_index(p, d)          # [cap, hd] -> flat offset
 
 
-def kv_plain_views(kvdesc):
-    """(k, v) as torch tensors [layers, heads, cap, hd] in natural order, whatever the layout."""
+def kv_plain_views(kvdesc, k_interleaved=False):
+    """(k, v) as torch tensors [layers, heads, cap, hd] in natural order, whatever the layout.
+    k_interleaved: the cache was written by a packed model, whose keys carry the rotation-pair
+    interleaved feature order (stored feature 2j + b is natural feature j + b*hd/2)."""
     L, Hk, cap, hd = kvdesc.k.shape
     if not kvdesc.tiled:
-        return kvdesc.k, kvdesc.v.permute(0, 1, 3, 2)
-    ki, vi = kv_maps(cap, hd)
-    ki = torch.from_numpy(ki).to(kvdesc.k.device).reshape(-1)
-    vi = torch.from_numpy(vi).to(kvdesc.k.device).reshape(-1)
-    kf = kvdesc.k.reshape(L, Hk, cap * hd)[:, :, ki].reshape(L, Hk, cap, hd)
-    vf = kvdesc.v.reshape(L, Hk, cap * hd)[:, :, vi].reshape(L, Hk, cap, hd)
+        kf, vf = kvdesc.k, kvdesc.v.permute(0, 1, 3, 2)
+    else:
+        ki, vi = kv_maps(cap, hd)
+        ki = torch.from_numpy(ki).to(kvdesc.k.device).reshape(-1)
+        vi = torch.from_numpy(vi).to(kvdesc.k.device).reshape(-1)
+        kf = kvdesc.k.reshape(L, Hk, cap * hd)[:, :, ki].reshape(L, Hk, cap, hd)
+        vf = kvdesc.v.reshape(L, Hk, cap * hd)[:, :, vi].reshape(L, Hk, cap, hd)
+    if k_interleaved:
+        nat = torch.arange(hd, device=kf.device)
+        kf = kf[..., 2 * (nat % (hd // 2)) + nat // (hd // 2)]
     return kf, vf
 
 

@@ -108,6 +108,54 @@ def test_prefill_crosses_chunk_boundaries():
         assert np.abs(vg[l] - kv.v[l][:299]).max() < 1e-4
 
 
+@pytest.mark.parametrize("shape_name", ["tiny_bf16", "tiny_gqa_bf16"])
+def test_packed_prefill_cache_matches_oracle(shape_name):
+    """Packed bf16 models rotate and store queries, keys and values in the epilogue of the fused Q/K/V
+    projection; the committed cache must hold the oracle's keys (read back through the interleaved feature
+    order of such models) and values, to bf16 accuracy."""
+    require_gpu()
+    say("packed prefill cache", shape_name)
+    sh = synth.SHAPES[shape_name]
+    w = synth.make_weights(sh, seed=2)
+    wn = synth.weights_to_numpy(w)
+    prompt = synth.zipf_prompt(sh.vocab, 150, seed=2).tolist()
+    eng = tr.Engine(sh, to_gpu(w), synth.tree15(), k=K, capacity=256)
+    assert eng.model.packed
+    eng.prefill(prompt)
+    torch.cuda.synchronize()
+    cfg = oracle_cfg(sh)
+    kv = O.KVCache(cfg, 256)
+    O.prefill(cfg, wn, kv, prompt[:-1])
+    kp, vp = kv_plain_views(eng.kv, k_interleaved=True)
+    kg = kp[:, :, :149, :].permute(0, 2, 1, 3).float().cpu().numpy()
+    vg = vp[:, :, :149, :].permute(0, 2, 1, 3).float().cpu().numpy()
+    for l in range(sh.n_layers):
+        ek = np.abs(kg[l] - kv.k[l][:149]).max() / np.abs(kv.k[l][:149]).max()
+        ev = np.abs(vg[l] - kv.v[l][:149]).max() / np.abs(kv.v[l][:149]).max()
+        say("layer", l, "relative K error", ek, "V error", ev)
+        assert ek < 2e-2 and ev < 2e-2
+
+
+def test_pack_weight_rope_interleaves_rows():
+    """y = x W^T through a matrix packed with tr_pack_weight_rope comes out with output feature
+    h*hd + 2j + b holding what feature h*hd + j + b*hd/2 holds with the plain packing."""
+    require_gpu()
+    n, K_, O_, hd = 33, 256, 512, 128
+    x = synth.normal_tensor((n, K_), 1.0, seed=4, dtype=torch.bfloat16)
+    wt = synth.uniform_tensor((O_, K_), float(np.sqrt(3.0 / K_)), seed=6, tensor_id=3, dtype=torch.bfloat16)
+    ctx = tr.Context(16, 8, [-1], [-1], 1)
+    ws = torch.empty(((n + 15) // 16 * 16 * K_ * 2 + 512 + n * O_ * 4 + 512), dtype=torch.uint8, device="cuda")
+    y0 = torch.zeros(n, O_, dtype=torch.float32, device="cuda")
+    y1 = torch.zeros_like(y0)
+    ctx.op_linear(x.cuda(), tr.pack_weight(wt.cuda()), y0, ws, packed=True, splits=1)
+    ctx.op_linear(x.cuda(), tr.pack_weight(wt.cuda(), rope_head_dim=hd), y1, ws, packed=True, splits=1)
+    o = np.arange(O_)
+    src = (o // hd) * hd + (o % hd) // 2 + ((o % hd) % 2) * (hd // 2)
+    assert np.array_equal(y1.cpu().numpy(), y0.cpu().numpy()[:, src])
+    with pytest.raises(tr.TRError):
+        tr.pack_weight(wt.cuda(), rope_head_dim=96)            # 512 is not a multiple of 96
+
+
 def test_capacity_is_checked_on_the_host():
     require_gpu()
     sh = synth.SHAPES["tiny"]
