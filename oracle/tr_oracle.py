@@ -15,6 +15,8 @@ What follows the paper, function by function
   forward_nodes   Section 2.2 equations: node i sees P(x | s, its ancestors), i.e.
                   tree attention (Section 2.2 "Tree Attention")
   tr_step / tr_generate / ar_generate   the decode loop of Sections 2.1 and 3
+  sample_tokens   Section 5.3 "Temperature Sampling": the model's token at a node is
+                  drawn from softmax(logits / T) instead of taken as the argmax
 
 The paper runs unmodified HuggingFace Llama-family models and does not restate the
 architecture.  The transformer here is the public Llama description: pre-RMSNorm
@@ -33,6 +35,15 @@ Readings taken where the paper is silent or garbled
   * prefill covers prompt[0..P-2]; the last prompt token is the first root; prefill
     does not touch M.
   * tree node n sits at position L + depth(n).
+  * temperature sampling (the paper reports results but gives no rule): the token
+    "the model outputs" at a node is drawn from softmax(logits / T); a draft is
+    correct when it equals the token drawn at its parent (the chain rule of Section
+    2.2 unchanged); the matrix still stores the top-k of the logits, as the paper
+    says it does.  The draw is the Gumbel-max form argmax_j(logits_j / T + g_j) with
+    noise g supplied by the caller per sequence position, so that the same noise
+    gives the same token whether the position is reached by a tree node or by plain
+    one-token decoding: TR under sampling then reproduces plain sampling token for
+    token.
 
 Precision: `dtype` is float64 by default (weights are float32 / bf16-representable
 values, converted on use); float32 is available for large shapes.
@@ -325,6 +336,20 @@ def prefill(cfg: Config, w: dict, kv: KVCache, tokens: Sequence[int], dtype=np.f
 
 
 # ----------------------------------------------------------------------------
+# temperature sampling (Section 5.3)
+# ----------------------------------------------------------------------------
+def sample_tokens(logits: np.ndarray, pos: Sequence[int], inv_temperature: float,
+                  noise: np.ndarray) -> np.ndarray:
+    """Token drawn at each row: argmax_j (logits[r, j] * (1/T) + noise[pos[r], j]), ties to the
+    smallest index.  With g ~ Gumbel(0, 1) this is a draw from softmax(logits / T) (Gumbel-max).
+    The arithmetic is fixed to float32 (one rounded multiply, one rounded add), because it decides
+    an integer: whoever repeats it in float32 gets the same tokens."""
+    y = (logits.astype(np.float32) * np.float32(inv_temperature)).astype(np.float32)
+    y = (y + noise[np.asarray(pos, dtype=np.int64)].astype(np.float32)).astype(np.float32)
+    return np.argmax(y, axis=1).astype(np.int64)            # first occurrence of the maximum
+
+
+# ----------------------------------------------------------------------------
 # decode loops
 # ----------------------------------------------------------------------------
 @dataclass
@@ -336,30 +361,33 @@ class StepResult:
 
 
 def integer_pipeline(M: np.ndarray, tree: Tree, S: np.ndarray, logits: np.ndarray, k: int,
-                     update_mode: str = "last", update_accepted_only: bool = False):
-    """Top-k, accept and matrix update from given logits (in place on M)."""
+                     update_mode: str = "last", update_accepted_only: bool = False, out=None):
+    """Top-k, accept and matrix update from given logits (in place on M).  `out` = the model's token
+    per node when it is not the argmax (temperature sampling)."""
     topk = np.stack([topk_ids(logits[n], k) for n in range(tree.n_nodes)])
-    acc = accept(S, topk[:, 0], tree)
+    acc = accept(S, topk[:, 0] if out is None else out, tree)
     update_matrix(M, S, topk, update_mode, acc.path if update_accepted_only else None)
     return topk, acc
 
 
 def tr_step(cfg: Config, w: dict, kv: KVCache, M: np.ndarray, tree: Tree, root: int, k: int,
             dtype=np.float64, row_independent: bool = False, update_mode: str = "last",
-            update_accepted_only: bool = False) -> StepResult:
-    """Draft (build_tree), verify (one forward), accept, update M, commit accepted K/V."""
+            update_accepted_only: bool = False, sampler=None) -> StepResult:
+    """Draft (build_tree), verify (one forward), accept, update M, commit accepted K/V.
+    sampler = (1/T, noise[position, vocab]) switches the model's tokens from argmax to draws."""
     S = build_tree(M, tree, root)
     L = kv.len
     pos = [L + int(d) for d in tree.depth]
     logits, nk, nv = forward_nodes(cfg, w, kv, S, pos, tree.paths, dtype, row_independent)
-    topk, acc = integer_pipeline(M, tree, S, logits, k, update_mode, update_accepted_only)
+    out = None if sampler is None else sample_tokens(logits, pos, sampler[0], sampler[1])
+    topk, acc = integer_pipeline(M, tree, S, logits, k, update_mode, update_accepted_only, out)
     commit(kv, nk, nv, acc.path)
     return StepResult(S, logits, topk, acc)
 
 
 def tr_generate(cfg: Config, w: dict, M: np.ndarray, tree: Tree, prompt: Sequence[int],
                 n_new: int, k: int, capacity: Optional[int] = None, dtype=np.float64,
-                row_independent: bool = False, on_step=None):
+                row_independent: bool = False, on_step=None, sampler=None):
     """Prefill prompt[:-1], then repeat tr_step from root = prompt[-1] until n_new tokens
     exist (overshoot truncated).  Returns (tokens, accepted_lengths, kv)."""
     capacity = capacity or (len(prompt) + n_new + tree.n_nodes + tree.n_layers)
@@ -367,7 +395,7 @@ def tr_generate(cfg: Config, w: dict, M: np.ndarray, tree: Tree, prompt: Sequenc
     prefill(cfg, w, kv, prompt[:-1], dtype, row_independent)
     root, out, lens = int(prompt[-1]), [], []
     while len(out) < n_new:
-        r = tr_step(cfg, w, kv, M, tree, root, k, dtype, row_independent)
+        r = tr_step(cfg, w, kv, M, tree, root, k, dtype, row_independent, sampler=sampler)
         out.extend(r.acc.emitted)
         lens.append(r.acc.n_accepted + 1)
         root = r.acc.bonus
@@ -377,16 +405,20 @@ def tr_generate(cfg: Config, w: dict, M: np.ndarray, tree: Tree, prompt: Sequenc
 
 
 def ar_generate(cfg: Config, w: dict, prompt: Sequence[int], n_new: int,
-                capacity: Optional[int] = None, dtype=np.float64, row_independent: bool = False):
-    """Plain greedy decoding (Section 2.1): one token per forward, x = argmax p."""
+                capacity: Optional[int] = None, dtype=np.float64, row_independent: bool = False,
+                sampler=None):
+    """Plain decoding (Section 2.1): one token per forward, x = argmax p, or a draw from
+    softmax(logits / T) when sampler = (1/T, noise[position, vocab]) is given."""
     capacity = capacity or (len(prompt) + n_new + 1)
     kv = KVCache(cfg, capacity, dtype)
     prefill(cfg, w, kv, prompt[:-1], dtype, row_independent)
     tok, out, all_logits = int(prompt[-1]), [], []
     for _ in range(n_new):
         logits, nk, nv = forward_nodes(cfg, w, kv, [tok], [kv.len], [[0]], dtype, row_independent)
+        pos = kv.len
         commit(kv, nk, nv, [0])
-        tok = int(topk_ids(logits[0], 1)[0])
+        tok = int(topk_ids(logits[0], 1)[0]) if sampler is None else \
+            int(sample_tokens(logits, [pos], sampler[0], sampler[1])[0])
         out.append(tok)
         all_logits.append(logits[0])
     return out, all_logits, kv

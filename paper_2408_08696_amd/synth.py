@@ -103,6 +103,16 @@ def uniform_tensor(shape: Sequence[int], scale: float, seed: int, tensor_id: int
     return out.view(*shape)
 
 
+def gumbel_noise(n_positions: int, vocab: int, seed: int = 0) -> torch.Tensor:
+    """Standard Gumbel noise g = -log(-log(u)), float32 [n_positions, vocab], u from the counter hash
+    (strictly inside (0, 1)): the random numbers a temperature-sampling run draws, one row per
+    sequence position, handed to both the oracle and the GPU path as an input."""
+    n = n_positions * vocab
+    idx = torch.arange(n, dtype=torch.int64)
+    u = ((_hash_u32(idx, seed, 0x51) >> 8).to(torch.float64) + 0.5) * (1.0 / (1 << 24))
+    return (-torch.log(-torch.log(u))).to(torch.float32).view(n_positions, vocab)
+
+
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 
