@@ -233,6 +233,38 @@ tr_status tr_accept_and_update(tr_ctx *ctx, tr_kv *kv, const int32_t *d_S, const
                                tr_step_out *d_out, tr_step_out *h_out, void *stream);
 
 /*
+ * Temperature sampling (Section 5.3 "Temperature Sampling").  The paper reports results under sampling
+ * without stating the rule; the reading taken here: the token the model emits at a node is drawn from
+ * softmax(logits / T) instead of taken as the argmax, a draft is correct when it equals the token drawn
+ * at its parent (the chain rule of Section 2.2 unchanged), and the matrix still stores the top-k of the
+ * logits.  The draw is the Gumbel-max form with noise the caller supplies per sequence position:
+ *
+ *   tr_op_sample: d_tokens[i] = argmax_j ( d_logits[i][j] * inv_temperature
+ *                                          + d_noise[(L + depth(i)) - noise_pos0][j] ),
+ *     ties to the smallest j, for the N nodes of the context's tree; the multiply and the add are
+ *     two separately rounded float32 operations.  d_logits [device] float32 [N, V] as written by
+ *     tr_verify_forward; d_noise [device] float32 [noise_rows, V], row r holding the noise of
+ *     sequence position noise_pos0 + r (standard Gumbel values give a draw from softmax(logits/T);
+ *     zeros give the greedy rule); d_tokens [device] int32 [N].  Call it between tr_verify_forward
+ *     and the accept call of the same step (L must not have moved).  Keying the noise by position
+ *     makes a tree node and a plain one-token step at the same position draw the same token, so a
+ *     run under sampling emits exactly the sequence plain sampling would.
+ *     Errors: TR_EINVAL (NULL, noise_pos0 < 0, noise_rows <= 0, inv_temperature not positive and
+ *     finite), TR_ECAPACITY (the table does not reach kv->len_bound + n_layers), TR_EHIP.  A position
+ *     below noise_pos0 cannot be detected on the host (L lives on the device): the kernel then
+ *     reads the table's first row.
+ *   tr_accept_and_update_sampled: tr_accept_and_update with d_tokens [device] int32 [N] in the place
+ *     of the first top-k column as "the token the model emits at node i".  Errors as there, plus
+ *     TR_EINVAL for a NULL d_tokens.
+ */
+tr_status tr_op_sample(tr_ctx *ctx, const tr_kv *kv, const float *d_logits, const float *d_noise,
+                       int32_t noise_pos0, int32_t noise_rows, float inv_temperature,
+                       int32_t *d_tokens, void *stream);
+tr_status tr_accept_and_update_sampled(tr_ctx *ctx, tr_kv *kv, const int32_t *d_S,
+                                       const int32_t *d_topk, const int32_t *d_tokens,
+                                       tr_step_out *d_out, tr_step_out *h_out_or_null, void *stream);
+
+/*
  * Prompt ingestion through the same kernels: runs d_tokens [device] int32 [n_tokens] causally
  * after the committed prefix (a chain is a tree whose node i has ancestors 0..i), commits their
  * keys/values and advances *kv->d_len and kv->len_bound by n_tokens.  No logits, no matrix

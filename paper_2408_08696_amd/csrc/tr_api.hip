@@ -227,8 +227,8 @@ tr_status tr_verify_forward(tr_ctx *c, const tr_model *m, tr_kv *kv, const int32
   return TR_OK;
 }
 
-tr_status tr_accept_and_update(tr_ctx *c, tr_kv *kv, const int32_t *d_S, const int32_t *d_topk, tr_step_out *d_out,
-                               tr_step_out *h_out, void *stream) {
+static tr_status accept_and_update(tr_ctx *c, tr_kv *kv, const int32_t *d_S, const int32_t *d_topk,
+                                   const int32_t *d_tokens, tr_step_out *d_out, tr_step_out *h_out, void *stream) {
   if (c == nullptr || d_S == nullptr || d_topk == nullptr || d_out == nullptr) return TR_EINVAL;
   tr_status s = check_kv(kv);
   if (s != TR_OK) return s;
@@ -237,7 +237,7 @@ tr_status tr_accept_and_update(tr_ctx *c, tr_kv *kv, const int32_t *d_S, const i
   { ProfScope empty(&c->prof, PC_EMPTY, st); } // an event pair around nothing: the bracket's own cost
   {
     ProfScope ps(&c->prof, PC_ACCEPT, st);
-    if (launch_accept_update(c, kv, d_S, d_topk, d_out, st) != hipSuccess) return TR_EHIP;
+    if (launch_accept_update(c, kv, d_S, d_topk, d_tokens, d_out, st) != hipSuccess) return TR_EHIP;
   }
   if (h_out != nullptr) {
     if (hipMemcpyAsync(h_out, d_out, sizeof(tr_step_out), hipMemcpyDeviceToHost, st) != hipSuccess) return TR_EHIP;
@@ -247,6 +247,31 @@ tr_status tr_accept_and_update(tr_ctx *c, tr_kv *kv, const int32_t *d_S, const i
     kv->len_bound += c->tree.n_layers;
   }
   return TR_OK;
+}
+
+tr_status tr_accept_and_update(tr_ctx *c, tr_kv *kv, const int32_t *d_S, const int32_t *d_topk, tr_step_out *d_out,
+                               tr_step_out *h_out, void *stream) {
+  return accept_and_update(c, kv, d_S, d_topk, nullptr, d_out, h_out, stream);
+}
+
+tr_status tr_accept_and_update_sampled(tr_ctx *c, tr_kv *kv, const int32_t *d_S, const int32_t *d_topk,
+                                       const int32_t *d_tokens, tr_step_out *d_out, tr_step_out *h_out, void *stream) {
+  if (d_tokens == nullptr) return TR_EINVAL;
+  return accept_and_update(c, kv, d_S, d_topk, d_tokens, d_out, h_out, stream);
+}
+
+tr_status tr_op_sample(tr_ctx *c, const tr_kv *kv, const float *d_logits, const float *d_noise, int32_t noise_pos0,
+                       int32_t noise_rows, float inv_temperature, int32_t *d_tokens, void *stream) {
+  if (c == nullptr || d_logits == nullptr || d_noise == nullptr || d_tokens == nullptr) return TR_EINVAL;
+  tr_status s = check_kv(kv);
+  if (s != TR_OK) return s;
+  if (noise_pos0 < 0 || noise_rows <= 0 || !(inv_temperature > 0.0f) || !(inv_temperature < 3.0e38f)) return TR_EINVAL;
+  // the deepest node sits at L + n_layers - 1 with L <= len_bound
+  if ((int64_t)kv->len_bound + c->tree.n_layers > (int64_t)noise_pos0 + noise_rows) return TR_ECAPACITY;
+  return launch_sample_tokens(c, kv, d_logits, d_noise, noise_pos0, noise_rows, inv_temperature, d_tokens,
+                              as_stream(stream)) == hipSuccess
+             ? TR_OK
+             : TR_EHIP;
 }
 
 tr_status tr_prefill(tr_ctx *c, const tr_model *m, tr_kv *kv, const int32_t *d_tokens, int32_t n_tokens, void *ws,

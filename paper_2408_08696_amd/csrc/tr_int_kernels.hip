@@ -279,6 +279,7 @@ hipError_t launch_matrix_update(const tr_ctx *c, const int32_t *d_S, const int32
 __global__ __launch_bounds__(TR_MAX_NODES) void k_accept_update(int32_t *__restrict__ M, int32_t V, int32_t k,
                                                                 TreeDev t, const int32_t *__restrict__ S,
                                                                 const int32_t *__restrict__ topk,
+                                                                const int32_t *__restrict__ tokens,
                                                                 int32_t *__restrict__ d_len,
                                                                 int32_t *__restrict__ step_L,
                                                                 tr_step_out *__restrict__ out, int32_t mode) {
@@ -292,7 +293,9 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_accept_update(int32_t *__restr
   if (live) {
     int tk = S[i];
     sS[i] = tk < 0 ? 0 : (tk >= V ? V - 1 : tk);
-    sOut[i] = topk[(size_t)i * k];
+    // the token the model emits at node i: its argmax, or the caller's draw under temperature sampling
+    int ot = tokens != nullptr ? tokens[i] : topk[(size_t)i * k];
+    sOut[i] = ot < 0 ? 0 : (ot >= V ? V - 1 : ot);
   }
   __syncthreads();
   const bool match = live && (i == 0 || sS[i] == sOut[t.parent[i]]);
@@ -374,10 +377,62 @@ __global__ __launch_bounds__(256) void k_compact_kv(T *__restrict__ K, T *__rest
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Temperature sampling (Section 5.3): the token drawn at node i is
+//   argmax_j ( logits[i][j] * inv_t + noise[L + depth(i) - pos0][j] ),   ties to the smallest j,
+// i.e. a draw from softmax(logits / T) when the noise is standard Gumbel.  The two float32 operations
+// are kept separate (no fused multiply-add): they decide an integer, and whoever repeats them rounds
+// the same way.  One workgroup per node.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_sample_tokens(const float *__restrict__ logits, const float *__restrict__ noise,
+                                                       int32_t V, int32_t pos0, int32_t noise_rows, float inv_t,
+                                                       const int32_t *__restrict__ depth,
+                                                       const int32_t *__restrict__ d_len, int32_t *__restrict__ tokens) {
+  __shared__ float sv[256];
+  __shared__ int32_t si[256];
+  const int i = blockIdx.x;
+  int row = *d_len + depth[i] - pos0;
+  row = row < 0 ? 0 : (row >= noise_rows ? noise_rows - 1 : row); // the host checked the range; never read outside
+  const float *lg = logits + (size_t)i * V;
+  const float *nz = noise + (size_t)row * V;
+  float best = -__builtin_huge_valf();
+  int bj = 0x7fffffff;
+  for (int j = threadIdx.x; j < V; j += 256) {
+    const float y = __fadd_rn(__fmul_rn(lg[j], inv_t), nz[j]);
+    if (y > best || bj == 0x7fffffff) { // j grows, so on equal values the earlier index stays
+      best = y;
+      bj = j;
+    }
+  }
+  sv[threadIdx.x] = best;
+  si[threadIdx.x] = bj;
+  __syncthreads();
+  for (int h = 128; h >= 1; h >>= 1) {
+    if (threadIdx.x < h) {
+      const float ov = sv[threadIdx.x + h];
+      const int oi = si[threadIdx.x + h];
+      if (oi != 0x7fffffff && (si[threadIdx.x] == 0x7fffffff || ov > sv[threadIdx.x] ||
+                               (ov == sv[threadIdx.x] && oi < si[threadIdx.x]))) {
+        sv[threadIdx.x] = ov;
+        si[threadIdx.x] = oi;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) tokens[i] = si[0];
+}
+
+hipError_t launch_sample_tokens(const tr_ctx *c, const tr_kv *kv, const float *d_logits, const float *d_noise,
+                                int32_t pos0, int32_t noise_rows, float inv_t, int32_t *d_tokens, hipStream_t st) {
+  hipLaunchKernelGGL(k_sample_tokens, dim3(c->tree.n_nodes), dim3(256), 0, st, d_logits, d_noise, c->V, pos0, noise_rows,
+                     inv_t, c->tree.depth, kv->d_len, d_tokens);
+  return hipGetLastError();
+}
+
 hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t *d_S, const int32_t *d_topk,
-                                tr_step_out *d_out, hipStream_t st) {
+                                const int32_t *d_tokens, tr_step_out *d_out, hipStream_t st) {
   hipLaunchKernelGGL(k_accept_update, dim3(1), dim3(TR_MAX_NODES), 0, st, c->d_M, c->V, c->k, c->tree, d_S,
-                     d_topk, kv->d_len, c->d_step_L, d_out, c->update_mode);
+                     d_topk, d_tokens, kv->d_len, c->d_step_L, d_out, c->update_mode);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int blocks = kv->n_layers * kv->n_kv_heads;

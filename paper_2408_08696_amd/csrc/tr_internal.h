@@ -146,8 +146,11 @@ hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t 
                        int32_t *d_topk, void *d_cand, hipStream_t s);
 size_t topk_scratch_bytes();
 hipError_t launch_matrix_update(const tr_ctx *c, const int32_t *d_S, const int32_t *d_topk, hipStream_t s);
+// d_tokens: the model's token per node, or NULL for the argmax (first top-k column)
 hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t *d_S,
-                                const int32_t *d_topk, tr_step_out *d_out, hipStream_t s);
+                                const int32_t *d_topk, const int32_t *d_tokens, tr_step_out *d_out, hipStream_t s);
+hipError_t launch_sample_tokens(const tr_ctx *c, const tr_kv *kv, const float *d_logits, const float *d_noise,
+                                int32_t pos0, int32_t noise_rows, float inv_t, int32_t *d_tokens, hipStream_t s);
 hipError_t launch_advance_len(int32_t *d_len, int32_t by, hipStream_t s);
 hipError_t launch_stream(const void *src, void *dst, size_t bytes, hipStream_t s);
 

@@ -72,6 +72,10 @@ _SIGS = {
                           C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
     "tr_accept_and_update": [C.c_void_p, C.POINTER(KV), C.c_void_p, C.c_void_p, C.c_void_p,
                              C.POINTER(StepOut), C.c_void_p],
+    "tr_accept_and_update_sampled": [C.c_void_p, C.POINTER(KV), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.POINTER(StepOut), C.c_void_p],
+    "tr_op_sample": [C.c_void_p, C.POINTER(KV), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float,
+                     C.c_void_p, C.c_void_p],
     "tr_prefill": [C.c_void_p, C.POINTER(Model), C.POINTER(KV), C.c_void_p, C.c_int32, C.c_void_p,
                    C.c_size_t, C.c_void_p],
     "tr_op_topk": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
@@ -182,11 +186,22 @@ class Context:
                                        _ptr(d_topk), _ptr(ws), ws.numel() * ws.element_size(), _stream()),
                "tr_verify_forward")
 
-    def accept_and_update(self, kv: "KVDesc", d_S, d_topk, d_out, sync: bool = False) -> Optional[StepOut]:
+    def accept_and_update(self, kv: "KVDesc", d_S, d_topk, d_out, sync: bool = False,
+                          d_tokens=None) -> Optional[StepOut]:
+        """d_tokens: the model's token per node when it is a draw (temperature sampling), else the argmax."""
         h = StepOut() if sync else None
-        _check(lib().tr_accept_and_update(self._h, C.byref(kv.c), _ptr(d_S), _ptr(d_topk), _ptr(d_out),
-                                          C.byref(h) if sync else None, _stream()), "tr_accept_and_update")
+        if d_tokens is None:
+            _check(lib().tr_accept_and_update(self._h, C.byref(kv.c), _ptr(d_S), _ptr(d_topk), _ptr(d_out),
+                                              C.byref(h) if sync else None, _stream()), "tr_accept_and_update")
+        else:
+            _check(lib().tr_accept_and_update_sampled(self._h, C.byref(kv.c), _ptr(d_S), _ptr(d_topk),
+                                                      _ptr(d_tokens), _ptr(d_out), C.byref(h) if sync else None,
+                                                      _stream()), "tr_accept_and_update_sampled")
         return h
+
+    def op_sample(self, kv: "KVDesc", d_logits, d_noise, inv_temperature: float, d_tokens, noise_pos0: int = 0) -> None:
+        _check(lib().tr_op_sample(self._h, C.byref(kv.c), _ptr(d_logits), _ptr(d_noise), noise_pos0,
+                                  d_noise.shape[0], inv_temperature, _ptr(d_tokens), _stream()), "tr_op_sample")
 
     def prefill(self, model: "ModelDesc", kv: "KVDesc", d_tokens, ws) -> None:
         _check(lib().tr_prefill(self._h, C.byref(model.c), C.byref(kv.c), _ptr(d_tokens), d_tokens.numel(),
@@ -327,6 +342,7 @@ class Engine:
         self.topk = torch.zeros(n, k, dtype=torch.int32, device=device)
         self.logits = torch.zeros(n, shape.vocab, dtype=torch.float32, device=device) if keep_logits else None
         self.out = torch.zeros(STEP_OUT_INTS, dtype=torch.int32, device=device)
+        self.tokens = None                              # drawn tokens per node (temperature sampling)
         self.root = self.out[3:4]                       # next_root field of tr_step_out
 
     def prefill(self, prompt: Sequence[int]) -> None:
@@ -338,7 +354,16 @@ class Engine:
             self.ctx.prefill(self.model, self.kv, toks[:-1].contiguous(), self.ws)
         self.root.copy_(toks[-1:])
 
-    def step(self, sync: bool = False) -> Optional[StepOut]:
+    def step(self, sync: bool = False, sampler=None) -> Optional[StepOut]:
+        """sampler = (1/T, noise [positions, vocab] float32 device tensor): temperature sampling."""
         self.ctx.build_tree(self.root, self.S)
         self.ctx.verify_forward(self.model, self.kv, self.S, self.logits, self.topk, self.ws)
-        return self.ctx.accept_and_update(self.kv, self.S, self.topk, self.out, sync)
+        if sampler is None:
+            return self.ctx.accept_and_update(self.kv, self.S, self.topk, self.out, sync)
+        if self.logits is None:
+            raise ValueError("temperature sampling needs the logits: create the Engine with keep_logits=True")
+        if self.tokens is None:
+            import torch
+            self.tokens = torch.zeros(self.n_nodes, dtype=torch.int32, device=self.S.device)
+        self.ctx.op_sample(self.kv, self.logits, sampler[1], sampler[0], self.tokens)
+        return self.ctx.accept_and_update(self.kv, self.S, self.topk, self.out, sync, self.tokens)

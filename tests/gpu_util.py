@@ -32,11 +32,13 @@ def say(*a):
 
 
 def lockstep(eng, sh, w_np, tmpl, prompt, n_steps, M0, k=8, rel_tol=2e-2, abs_tol=None, dtype=np.float64,
-             label=""):
+             label="", sampler=None):
     """Teacher-forced parity of whole steps.  Each step the oracle starts from the same integer
     state as the GPU (root, M, committed tokens), its logits are compared under the tolerance, and
     its integer pipeline (top-k, accept, matrix update) is applied to the GPU's own logits and must
-    reproduce the GPU's integers bit for bit.  Returns per-step stats."""
+    reproduce the GPU's integers bit for bit.  Returns per-step stats.
+    sampler = (1/T, noise [positions, vocab] float32 numpy): temperature sampling on both sides; the
+    oracle's draws from the GPU's logits must equal the GPU's draws."""
     cfg = oracle_cfg(sh)
     tree = O.make_tree(tmpl.parent, tmpl.rank, k)
     eng.ctx.matrix_load(M0)
@@ -46,9 +48,10 @@ def lockstep(eng, sh, w_np, tmpl, prompt, n_steps, M0, k=8, rel_tol=2e-2, abs_to
     O.prefill(cfg, w_np, kv, list(prompt[:-1]), dtype)
     root = int(prompt[-1])
     stats = []
+    gpu_sampler = None if sampler is None else (sampler[0], torch.from_numpy(sampler[1]).cuda())
     for step in range(n_steps):
         say(f"lockstep {label} step {step} L={kv.len}")
-        h = eng.step(sync=True)
+        h = eng.step(sync=True, sampler=gpu_sampler)
         S = O.build_tree(M, tree, root)
         assert eng.S.cpu().tolist() == S.tolist(), f"step {step}: tree differs"
         pos = [kv.len + int(d) for d in tree.depth]
@@ -60,7 +63,11 @@ def lockstep(eng, sh, w_np, tmpl, prompt, n_steps, M0, k=8, rel_tol=2e-2, abs_to
             assert err.max() <= abs_tol, f"step {step}: logits differ by {err.max()}"
         else:
             assert (err <= rel_tol * scale).all(), f"step {step}: rel err {np.max(err / scale)}"
-        topk, acc = O.integer_pipeline(M, tree, S, lg, k)          # oracle integers on the GPU's logits
+        out = None
+        if sampler is not None:
+            out = O.sample_tokens(eng.logits.cpu().numpy(), pos, sampler[0], sampler[1])
+            assert eng.tokens.cpu().tolist() == out.tolist(), f"step {step}: drawn tokens differ"
+        topk, acc = O.integer_pipeline(M, tree, S, lg, k, out=out)  # oracle integers on the GPU's logits
         assert np.array_equal(eng.topk.cpu().numpy().astype(np.int64), topk), f"step {step}: top-k differs"
         assert h.n_accepted == acc.n_accepted and h.winner == acc.winner
         assert list(h.path[:h.n_emitted]) == acc.path and list(h.emitted[:h.n_emitted]) == acc.emitted

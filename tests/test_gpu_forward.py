@@ -85,6 +85,25 @@ def test_small_shapes_lockstep(shape_name, tmpl_name):
     say(stats)
 
 
+@pytest.mark.parametrize("shape_name,temperature", [("tiny", 0.8), ("tiny_bf16", 0.5), ("tiny_gqa_bf16", 1.0)])
+def test_temperature_sampling_lockstep(shape_name, temperature):
+    """Whole steps under temperature sampling (Section 5.3): drawn tokens, accept lengths, emitted
+    tokens, the matrix and the cache length must follow the oracle's rule applied to the GPU's logits."""
+    require_gpu()
+    sh = synth.SHAPES[shape_name]
+    tmpl = synth.tree80()
+    w = synth.make_weights(sh, seed=4)
+    wn = synth.weights_to_numpy(w)
+    prompt = synth.zipf_prompt(sh.vocab, 70, seed=4).tolist()
+    n_steps = 6
+    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=70 + n_steps * tmpl.n_layers + tmpl.n_nodes + 32)
+    noise = synth.gumbel_noise(70 + (n_steps + 1) * tmpl.n_layers, sh.vocab, seed=9).numpy()
+    stats, _ = lockstep(eng, sh, wn, tmpl, prompt, n_steps, synth.init_matrix(sh.vocab, K),
+                        abs_tol=1e-4 if sh.dtype == "f32" else None, label=f"{shape_name} T={temperature}",
+                        sampler=(1.0 / temperature, noise))
+    say(stats)
+
+
 def test_prefill_crosses_chunk_boundaries():
     """A 300-token prompt goes through three chain chunks (128 + 128 + 43); the cache must equal
     the oracle's causal prefill."""

@@ -238,3 +238,32 @@ def test_update_example_first_on_gpu(golden):
     assert M[1].tolist() == [int(x) for x in g["expect_first 1"][0]]
     with pytest.raises(tr.TRError):
         ctx.set_update_mode(4)
+
+
+@pytest.mark.parametrize("V,L", [(1000, 0), (32000, 513), (128256, 37)])
+def test_sample_tokens_match_oracle(V, L):
+    """Temperature sampling draw (Section 5.3): argmax of logits / T + position-keyed noise in the stated
+    float32 arithmetic, ties to the smallest index, bit-exact against the oracle."""
+    require_gpu()
+    say("sample", V, L)
+    t = synth.tree80()
+    tree = O.make_tree(t.parent, t.rank, 8)
+    ctx = tr.Context(V, 8, t.parent, t.rank, t.n_layers)
+    sh = synth.ModelShape("s", 1, 128, 1, 1, 128, 128, V, "bf16")
+    kv = tr.KVDesc(sh, L + 128)
+    kv.reset(L)
+    logits = synth.normal_tensor((t.n_nodes, V), 3.0, seed=V, dtype=torch.float32)
+    logits[3, 5] = logits[3, V - 1] = 50.0                       # planted tie: index 5 must win with equal noise
+    noise = synth.gumbel_noise(L + t.n_layers, V, seed=L)
+    noise[L + int(tree.depth[3]), 5] = noise[L + int(tree.depth[3]), V - 1] = 0.0
+    tokens = torch.zeros(t.n_nodes, dtype=torch.int32, device="cuda")
+    pos = [L + int(d) for d in tree.depth]
+    for inv_t in (1.0 / 0.3, 1.0, 2.0):
+        ctx.op_sample(kv, logits.cuda(), noise.cuda(), inv_t, tokens)
+        want = O.sample_tokens(logits.numpy(), pos, inv_t, noise.numpy())
+        assert tokens.cpu().tolist() == want.tolist()
+        assert want[3] == 5
+    with pytest.raises(tr.TRError):
+        ctx.op_sample(kv, logits.cuda(), noise[:L + 2].cuda(), 1.0, tokens)     # table too short for the tree
+    with pytest.raises(tr.TRError):
+        ctx.op_sample(kv, logits.cuda(), noise.cuda(), 0.0, tokens)
