@@ -14,15 +14,20 @@
 // 16*nt + l%16.
 //
 // Mapping.  One workgroup owns up to NW consecutive out-tiles (16*NW output features; the tiles are dealt
-// evenly over the workgroups) and one of `splits` K-ranges; its GW = 8 wavefronts (4 in the NW = 8 variant) take interleaved k-tiles of that range, keep PF k-steps of loads in flight
-// in registers, and reduce through LDS at the end, each wave ending up with (and storing) its share of
-// the output tiles.  splits > 1 writes one partial
-// result per split (summed in a fixed order by the consumer), so results are run-to-run deterministic.
+// evenly over the workgroups) and one of `splits` K-ranges; its GW = 8 wavefronts (4 in the NW = 8
+// variant) take interleaved k-tiles of that range, keep PF k-steps of loads in flight in registers, and
+// reduce through LDS at the end, each wave ending up with (and storing) its share of the output tiles.
+// splits > 1 writes one partial result per split (summed in a fixed order by the consumer), so results
+// are run-to-run deterministic.
 //
 // Why NW is large.  Every workgroup reads the whole activation block of its K-range from L2 (16*NT rows),
 // so L2 carries (1 + 16*NT / (16*NW)) bytes per weight byte; measured L2->CU throughput on MI355X is only
-// about twice the HBM rate, so the kernel stays HBM-bound only while NW >= NT.  launch_gemm_mfma picks
-// (NW, splits) to get close to one workgroup per compute unit with NW as large as registers allow.
+// about twice the HBM rate, so the kernel stays HBM-bound only while NW >= NT.  gemm_choose picks
+// (NW, workgroups, splits) from a cost model of exactly this trade, close to one workgroup per compute
+// unit with NW as large as the register file allows.
+//
+// Epilogues: plain float32 store (per K-split), gate/up pairs through SwiGLU into the next GEMM's operand
+// order, or for the fused Q/K/V projection RoPE plus the query and KV-cache writes (GemmRope).
 #include "tr_kernels.h"
 
 namespace tr {
