@@ -53,6 +53,8 @@ SHAPES: Dict[str, ModelShape] = {
     "tiny_gqa_bf16": ModelShape("tiny_gqa_bf16", 2, 512, 4, 2, 128, 1376, 4096, "bf16"),
     # bf16 shape the packed layout does not cover (d_ffn not a multiple of 32): generic kernels
     "tiny_odd_bf16": ModelShape("tiny_odd_bf16", 2, 192, 3, 3, 64, 500, 1000, "bf16"),
+    # packed projections with a head width the matrix-core attention does not take (generic attention, plain KV)
+    "tiny_hd64_bf16": ModelShape("tiny_hd64_bf16", 2, 256, 4, 2, 64, 672, 2048, "bf16"),
     "7b": ModelShape("7b", 32, 4096, 32, 32, 128, 11008, 32000, "bf16"),
     "13b": ModelShape("13b", 40, 5120, 40, 40, 128, 13824, 32000, "bf16"),
     "70b": ModelShape("70b", 80, 8192, 64, 8, 128, 28672, 128256, "bf16"),

@@ -66,19 +66,23 @@ def test_tiny_fp32_free_running(tmpl_name):
                                                   ("tiny_bf16", "tree81"), ("tiny_bf16", "wide128"),
                                                   ("tiny_bf16", "single"), ("tiny", "tree80"),
                                                   ("tiny_odd_bf16", "tree80"), ("tiny_bf16:rowmajor", "tree15"),
-                                                  ("tiny_bf16", "prefix48"), ("tiny_gqa_bf16", "prefix97")])
+                                                  ("tiny_bf16", "prefix48"), ("tiny_gqa_bf16", "prefix97"),
+                                                  ("tiny_hd64_bf16", "tree80"), ("tiny_gqa_bf16:plainkv", "tree80")])
 def test_small_shapes_lockstep(shape_name, tmpl_name):
     require_gpu()
-    pack = None
+    pack, kv_tiled = None, None
     if shape_name.endswith(":rowmajor"):
         shape_name, pack = shape_name.split(":")[0], False    # bf16 through the generic kernels
+    if shape_name.endswith(":plainkv"):
+        shape_name, kv_tiled = shape_name.split(":")[0], False  # packed projections, position-major cache
     sh = synth.SHAPES[shape_name]
     tmpl = (synth.prefix_template(int(tmpl_name[6:])) if tmpl_name.startswith("prefix")
             else synth.TEMPLATES[tmpl_name]())
     w = synth.make_weights(sh, seed=1)
     prompt = synth.zipf_prompt(sh.vocab, 150, seed=3, ngram=8).tolist()
-    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=512, pack=pack)
+    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=512, pack=pack, kv_tiled=kv_tiled)
     assert eng.model.packed == (tr.can_pack(sh) if pack is None else pack)
+    assert eng.kv.tiled == ((sh.dtype == "bf16" and sh.head_dim == 128) if kv_tiled is None else kv_tiled)
     abs_tol = 1e-4 if sh.dtype == "f32" else None
     stats, _ = lockstep(eng, sh, synth.weights_to_numpy(w), tmpl, prompt, 6, synth.init_matrix(sh.vocab, K),
                         abs_tol=abs_tol, label=f"{shape_name}/{tmpl_name}")
