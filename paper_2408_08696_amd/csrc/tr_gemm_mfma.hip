@@ -296,7 +296,7 @@ bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O) {
 static bool variant_ok(int NT, int p, bool swiglu) {
   const int wt = swiglu ? 2 * p : p;
   if (wt == 8) return NT == 4 || NT == 5;
-  if (wt == 6) return NT <= 5;
+  if (wt == 6) return true; // eight waves up to 5 row tiles, the four-wave form beyond
   if (swiglu) return wt == 2 || wt == 4;
   return wt >= 1 && wt <= 4;
 }
@@ -374,6 +374,8 @@ static hipError_t launch_nt(const GemmArgs &g, hipStream_t st) {
     }
     if constexpr (NT <= 5) {
       if (p == 3) return launch_k<NT, 3, GEMM_SWIGLU>(g, st);
+    } else {
+      if (p == 3) return launch_k<NT, 3, GEMM_SWIGLU, 4>(g, st);
     }
     if (p == 2) return launch_k<NT, 2, GEMM_SWIGLU>(g, st);
     if (p == 1) return launch_k<NT, 1, GEMM_SWIGLU>(g, st);
@@ -384,6 +386,8 @@ static hipError_t launch_nt(const GemmArgs &g, hipStream_t st) {
   }
   if constexpr (NT <= 5) {
     if (p == 6) return launch_k<NT, 6, GEMM_STORE>(g, st);
+  } else {
+    if (p == 6) return launch_k<NT, 6, GEMM_STORE, 4>(g, st);
   }
   switch (p) {
   case 1: return launch_k<NT, 1, GEMM_STORE>(g, st);
