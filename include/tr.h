@@ -198,6 +198,26 @@ tr_status tr_pack_weight(const void *d_src, void *d_dst, int32_t out_f, int32_t 
 tr_status tr_pack_weight_rope(const void *d_src, void *d_dst, int32_t out_f, int32_t in_f,
                               int32_t head_dim, void *stream);
 
+/*
+ * Launch plan of one packed projection (diagnostic; touches no GPU).  For n_rows activation rows
+ * (tree nodes, Section 2.2: all nodes of the draft tree go through the model in one forward) and a
+ * weight of [out_f, in_f], reports what tr_verify_forward would launch: plan[0] = most 16-row weight
+ * tiles one workgroup owns (gate/up tile pairs when fused_pair != 0, where out_f counts one of the two
+ * matrices), plan[1] = workgroups per split of the input dimension, plan[2] = splits of the input
+ * dimension (1 .. max_splits; always 1 when fused_pair).  plan is [host], 3 values.
+ * TR_EINVAL for null plan, max_splits < 1, or a shape the packed kernels do not take (n_rows outside
+ * 1..TR_MAX_NODES, in_f or out_f not a multiple of 32).
+ */
+tr_status tr_plan_projection(int32_t n_rows, int32_t in_f, int32_t out_f, int32_t fused_pair,
+                             int32_t max_splits, int32_t *plan);
+
+/*
+ * Key-axis splits the tree-attention kernel (Section 2.2 "Tree Attention") would use for n_heads query
+ * heads and a host bound len_bound on committed length + tree nodes (diagnostic; touches no GPU).
+ * splits is [host].  TR_EINVAL for null splits, n_heads < 1 or len_bound < 1.
+ */
+tr_status tr_plan_attention(int32_t n_heads, int32_t len_bound, int32_t *splits);
+
 /* Bytes of [device] workspace tr_verify_forward / tr_prefill need for this model (256-aligned). */
 tr_status tr_workspace_bytes(const tr_ctx *ctx, const tr_model *model, size_t *bytes);
 

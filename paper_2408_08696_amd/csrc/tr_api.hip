@@ -202,6 +202,20 @@ tr_status tr_build_tree(tr_ctx *c, const int32_t *d_root, int32_t *d_S, void *st
   return launch_build_tree(c, d_root, d_S, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;
 }
 
+tr_status tr_plan_projection(int32_t n_rows, int32_t in_f, int32_t out_f, int32_t fused_pair, int32_t max_splits,
+                             int32_t *plan) {
+  if (plan == nullptr || max_splits < 1 || !gemm_mfma_supported(n_rows, in_f, out_f)) return TR_EINVAL;
+  const int32_t tiles = out_f / 16;
+  gemm_choose(n_rows, in_f, tiles, fused_pair != 0, fused_pair != 0 ? 1 : max_splits, &plan[0], &plan[1], &plan[2]);
+  return TR_OK;
+}
+
+tr_status tr_plan_attention(int32_t n_heads, int32_t len_bound, int32_t *splits) {
+  if (splits == nullptr || n_heads < 1 || len_bound < 1) return TR_EINVAL;
+  *splits = attn_choose_splits(n_heads, len_bound);
+  return TR_OK;
+}
+
 tr_status tr_workspace_bytes(const tr_ctx *c, const tr_model *m, size_t *bytes) {
   if (c == nullptr || bytes == nullptr) return TR_EINVAL;
   tr_status s = check_model(m);

@@ -68,6 +68,8 @@ _SIGS = {
     "tr_matrix_store": [C.c_void_p, C.c_void_p],
     "tr_build_tree": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "tr_workspace_bytes": [C.c_void_p, C.POINTER(Model), C.POINTER(C.c_size_t)],
+    "tr_plan_projection": [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)],
+    "tr_plan_attention": [C.c_int32, C.c_int32, C.POINTER(C.c_int32)],
     "tr_verify_forward": [C.c_void_p, C.POINTER(Model), C.POINTER(KV), C.c_void_p, C.c_void_p,
                           C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
     "tr_accept_and_update": [C.c_void_p, C.POINTER(KV), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -237,6 +239,20 @@ class Context:
         _check(lib().tr_op_linear(self._h, _ptr(d_x), _ptr(d_w), dt, TR_PACKED if packed else TR_ROW_MAJOR,
                                   d_x.shape[0], d_x.shape[1], d_w.shape[0], splits, _ptr(d_y), _ptr(ws),
                                   0 if ws is None else ws.numel() * ws.element_size(), _stream()), "tr_op_linear")
+
+
+def plan_projection(n_rows: int, in_f: int, out_f: int, fused_pair: bool = False, max_splits: int = 4):
+    """(weight tiles per workgroup, workgroups per split, splits) of one packed projection launch."""
+    plan = (C.c_int32 * 3)()
+    _check(lib().tr_plan_projection(n_rows, in_f, out_f, int(fused_pair), max_splits, plan), "tr_plan_projection")
+    return tuple(plan)
+
+
+def plan_attention(n_heads: int, len_bound: int) -> int:
+    """Key-axis splits of one tree-attention launch."""
+    s = C.c_int32()
+    _check(lib().tr_plan_attention(n_heads, len_bound, C.byref(s)), "tr_plan_attention")
+    return s.value
 
 
 def op_stream(src, dst=None) -> None:

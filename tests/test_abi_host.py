@@ -84,3 +84,63 @@ def test_default_templates_are_accepted_by_the_host_check():
         assert t.parent[0] == -1 and t.rank[0] == -1
         assert all(0 <= t.parent[i] < i for i in range(1, t.n_nodes))
         assert t.n_nodes <= tr.TR_MAX_NODES and t.n_layers <= tr.TR_MAX_LAYERS
+
+
+# ---- launch planners (host logic only) ----
+def _variant_exists(nt, p, fused):
+    """Kernel variants the projection source instantiates, by weight tiles per workgroup."""
+    wt = 2 * p if fused else p
+    if wt == 8:
+        return nt in (4, 5)
+    if wt == 6:
+        return True
+    return wt in ((2, 4) if fused else (1, 2, 3, 4))
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_projection_plans_cover_every_tile_once(lib, fused):
+    for n in (1, 15, 16, 17, 48, 64, 80, 81, 96, 112, 128):
+        for in_f, out_f in ((256, 256), (4096, 4096), (4096, 12288), (4096, 11008), (11008, 4096), (5120, 13824),
+                            (8192, 28672), (28672, 8192), (4096, 32000), (4096, 128256), (64, 32), (288, 96)):
+            for ms in (1, 2, 4):
+                p, groups, splits = tr.plan_projection(n, in_f, out_f, fused, ms)
+                tiles = out_f // 16
+                assert _variant_exists((n + 15) // 16, p, fused), (n, in_f, out_f, p)
+                assert 1 <= groups <= tiles and groups * p >= tiles       # each tile has exactly one owner
+                assert -(-tiles // groups) <= p                             # largest share fits the variant
+                assert splits in (1, 2, 4) and splits <= (1 if fused else ms)
+                assert splits == 1 or (in_f // 32) // splits >= 8           # every wave keeps >= 1 k-tile
+
+
+def test_projection_plan_rejects_bad_shapes(lib):
+    plan = (C.c_int32 * 3)()
+    assert lib.tr_plan_projection(80, 4096, 4096, 0, 4, None) == tr.TR_EINVAL
+    assert lib.tr_plan_projection(0, 4096, 4096, 0, 4, plan) == tr.TR_EINVAL
+    assert lib.tr_plan_projection(129, 4096, 4096, 0, 4, plan) == tr.TR_EINVAL
+    assert lib.tr_plan_projection(80, 4100, 4096, 0, 4, plan) == tr.TR_EINVAL
+    assert lib.tr_plan_projection(80, 4096, 4100, 0, 4, plan) == tr.TR_EINVAL
+    assert lib.tr_plan_projection(80, 4096, 4096, 0, 0, plan) == tr.TR_EINVAL
+
+
+def test_projection_plans_of_the_7b_step_fill_the_chip(lib):
+    # the five projections of a 7B layer at the 80-node tree: every plan puts work on >= 230 of 256 CUs
+    for in_f, out_f, fused, ms in ((4096, 12288, False, 1), (4096, 4096, False, 4), (4096, 11008, True, 1),
+                                   (11008, 4096, False, 4), (4096, 32000, False, 1)):
+        p, groups, splits = tr.plan_projection(80, in_f, out_f, fused, ms)
+        assert groups * splits >= 230, (in_f, out_f, p, groups, splits)
+
+
+def test_attention_plan(lib):
+    s = C.c_int32()
+    assert lib.tr_plan_attention(32, 600, None) == tr.TR_EINVAL
+    assert lib.tr_plan_attention(0, 600, C.byref(s)) == tr.TR_EINVAL
+    assert lib.tr_plan_attention(32, 0, C.byref(s)) == tr.TR_EINVAL
+    for H in (1, 8, 32, 40, 64, 256):
+        prev = 1
+        for L in (1, 31, 32, 33, 64, 100, 600, 2048, 8192, 65536):
+            n = tr.plan_attention(H, L)
+            assert n >= 1 and n & (n - 1) == 0 and n <= 16
+            assert n == 1 or 2 * (n // 2) <= -(-L // 32)    # every split owns at least one 32-key tile
+            assert n == 1 or H * (n // 2) < 256              # splitting stops once the chip is full
+            assert n >= prev                                 # never fewer splits for a longer context
+            prev = n
