@@ -15,8 +15,9 @@
 //
 // Mask: key position p is visible to node i when p < L (committed prefix), or L <= p < L + N and bit
 // p - L of the node's ancestor mask is set.  Invisible keys get probability exactly 0.
-// With more than one split, each writes (max, sum, unnormalised O) per node and k_attn_merge combines
-// them in split order.
+// With more than one split, split s owns tiles s, s + nsplit, ...; each writes (max, sum, normalised O in
+// half precision) per node and k_attn_merge combines them in split order.  K/V are read with streaming
+// loads: they are used once per call and would otherwise push the activations out of L2.
 #include "tr_kernels.h"
 
 namespace tr {
@@ -26,6 +27,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 
 __device__ inline f32x4 mfma16a(const u32x4 &a, const u32x4 &b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -50,12 +52,9 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
   const int r = lane & 15, g = lane >> 4;
   const int h = blockIdx.x, split = blockIdx.y;
   const int hk = h / (H / Hkv);
-  const int L = *d_len;
-  const int total = L + n;
-  const int n_tiles = (total + 31) >> 5;
-  const int per = (n_tiles + nsplit - 1) / nsplit;
-  const int t0 = split * per;
-  const int t1 = t0 + per < n_tiles ? t0 + per : n_tiles;
+  // split s owns tiles s, s + nsplit, s + 2 nsplit, ...: its first tile does not depend on the committed
+  // length, so that fetch is issued before the length has arrived, and the masked tiles at the end of
+  // the sequence spread over the splits
 
   const int node = wave * 16 + r;
   const int node_c = node < n ? node : n - 1;
@@ -87,7 +86,8 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
       const int s = tid + i * THREADS;
-      if (s < SLOTS) stage[i] = s < 512 ? Kh[(size_t)tile * 512 + s] : Vh[(size_t)tile * 512 + (s - 512)];
+      if (s < SLOTS)
+        stage[i] = __builtin_nontemporal_load(s < 512 ? Kh + (size_t)tile * 512 + s : Vh + (size_t)tile * 512 + (s - 512));
     }
   };
   auto publish = [&](int buf) {
@@ -102,12 +102,15 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
   // minimal: tiles that lie wholly in the committed prefix skip the mask, the scale is folded into the
   // exponent with one fma, the accumulators are rescaled only when some lane's maximum moved, and the
   // bf16 rounding of the probabilities is the hardware's packed conversion.
-  if (t0 < t1) fetch(t0);
-  for (int t = t0; t < t1; ++t) {
-    const int buf = (t - t0) & 1;
+  if ((split + 1) * 32 <= cap) fetch(split); // inside the cache allocation even if beyond the sequence
+  const int L = *d_len;
+  const int total = L + n;
+  const int n_tiles = (total + 31) >> 5;
+  int buf = 0;
+  for (int t = split; t < n_tiles; t += nsplit, buf ^= 1) {
     publish(buf);
     __syncthreads();
-    if (t + 1 < t1) fetch(t + 1);
+    if (t + nsplit < n_tiles) fetch(t + nsplit);
     const u32x4 *kt = lds[buf];
     const u32x4 *vt = lds[buf] + 512;
 
@@ -180,9 +183,9 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
     for (int dt = 0; dt < 8; ++dt) acc[dt] = mfma16a(vt[dt * 64 + lane], pf, acc[dt]);
   }
   const float lsum = accl[0];
-  if (node >= n) return;
 
   if (nsplit == 1) {
+    if (node >= n) return;
     const float inv = 1.0f / lsum;
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
@@ -192,37 +195,53 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
       o.z = f32_to_bf16(acc[dt][2] * inv); o.w = f32_to_bf16(acc[dt][3] * inv);
       const size_t idx = out_row_tiles > 0 ? act_frag_index(node, h * 128 + d, out_row_tiles)
                                            : ((size_t)node * H + h) * 128 + d;
-      *reinterpret_cast<ushort4 *>(out + idx) = o;
+      store_stream(out + idx, o);
     }
     return;
   }
-  const size_t row = ((size_t)split * H + h) * NP + node;
-  if (g == 0) {
-    part_ml[row * 2] = m;
-    part_ml[row * 2 + 1] = lsum;
+  // a split's partial result is its own normalised output (a convex combination of V rows, so it fits
+  // half precision with 2^-11 relative error, below the bf16 rounding of the merged output) plus (m, l).
+  // The wave's 16 x 128 block is turned through LDS so that a node's 256 bytes leave as whole lines.
+  const size_t row0 = ((size_t)split * H + h) * NP + wave * 16;
+  if (g == 0 && node < n) {
+    part_ml[(row0 + r) * 2] = m;
+    part_ml[(row0 + r) * 2 + 1] = lsum;
   }
+  const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+  __syncthreads(); // every wave is done with the last K/V tile
+  // row r keeps its 16-byte chunk c at slot c ^ r, so the 16 rows of one store hit distinct banks
+  char *blk = reinterpret_cast<char *>(&lds[0][0]) + wave * 4096;
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt)
-    *reinterpret_cast<float4 *>(part_acc + row * 128 + 16 * dt + 4 * g) =
-        float4{acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]};
+    *reinterpret_cast<f16x4 *>(blk + r * 256 + (((2 * dt + (g >> 1)) ^ r) << 4) + 8 * (g & 1)) =
+        __builtin_convertvector(acc[dt] * inv, f16x4);
+  // the wave reads back only what it wrote itself; its LDS operations complete in order
+  asm volatile("" ::: "memory");
+  u32x4 *pa = reinterpret_cast<u32x4 *>(part_acc);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = i * 64 + lane, rr = c >> 4, cc = c & 15;
+    const u32x4 v = *reinterpret_cast<const u32x4 *>(blk + rr * 256 + ((cc ^ rr) << 4));
+    if (wave * 16 + rr < n) pa[(row0 + rr) * 16 + cc] = v; // plain store: the merge pass finds these in L2
+  }
 }
 
-// out[node, h, :] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max m); splits without visible keys
-// (l_s == 0) contribute nothing.  Block (8 nodes, head), 32 threads x 4 features per node; all loads of a
-// thread are issued before any arithmetic.
+// out[node, h, :] = sum_s w_s o_s / sum_s w_s with w_s = l_s 2^(m_s - max m), o_s the split's normalised
+// output; splits without visible keys (l_s == 0) contribute nothing.  Block (8 nodes, head), 32 threads x
+// 4 features per node; all loads of a thread are issued before any arithmetic.
 __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ part_ml, const float *__restrict__ part_acc,
                                                     int32_t H, int32_t n, int32_t nsplit, bf16_t *__restrict__ out,
                                                     int32_t out_row_tiles) {
   const int node = blockIdx.x * 8 + (threadIdx.x >> 5), h = blockIdx.y, d = (threadIdx.x & 31) * 4;
   if (node >= n) return;
   float2 ml[ATTN_MAX_SPLITS];
-  float4 av[ATTN_MAX_SPLITS];
+  f16x4 av[ATTN_MAX_SPLITS];
 #pragma unroll
   for (int s = 0; s < ATTN_MAX_SPLITS; ++s) {
     if (s < nsplit) {
       const size_t row = ((size_t)s * H + h) * NP + node;
       ml[s] = *reinterpret_cast<const float2 *>(part_ml + row * 2);
-      av[s] = *reinterpret_cast<const float4 *>(part_acc + row * 128 + d);
+      av[s] = reinterpret_cast<const f16x4 *>(part_acc)[row * 32 + (d >> 2)];
     }
   }
   float M = NEG_BIG;
@@ -234,9 +253,10 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
 #pragma unroll
   for (int s = 0; s < ATTN_MAX_SPLITS; ++s) {
     if (s < nsplit && ml[s].y > 0.f) {
-      const float w = exp2f(ml[s].x - M);
-      den += w * ml[s].y;
-      num.x += w * av[s].x; num.y += w * av[s].y; num.z += w * av[s].z; num.w += w * av[s].w;
+      const float w = exp2f(ml[s].x - M) * ml[s].y;
+      den += w;
+      num.x += w * (float)av[s][0]; num.y += w * (float)av[s][1];
+      num.z += w * (float)av[s][2]; num.w += w * (float)av[s][3];
     }
   }
   const float inv = 1.0f / den;
@@ -245,7 +265,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
   o.z = f32_to_bf16(num.z * inv); o.w = f32_to_bf16(num.w * inv);
   const size_t idx = out_row_tiles > 0 ? act_frag_index(node, h * 128 + d, out_row_tiles)
                                        : ((size_t)node * H + h) * 128 + d;
-  *reinterpret_cast<ushort4 *>(out + idx) = o;
+  store_stream(out + idx, o);
 }
 
 bool attn_mfma_supported(int32_t hd, int32_t n) { return hd == 128 && n >= 1 && n <= TR_MAX_NODES; }

@@ -281,7 +281,7 @@ __global__ __launch_bounds__(GW * 64) void k_gemm_mfma(GemmArgs g) {
       hv.z = live ? f32_to_bf16(gt[2] / (1.0f + __expf(-gt[2])) * up[2]) : (bf16_t)0;
       hv.w = live ? f32_to_bf16(gt[3] / (1.0f + __expf(-gt[3])) * up[3]) : (bf16_t)0;
       const size_t slot = ((size_t)(o >> 5) * NT + t) * 64 + r + 16 * ((o & 31) >> 3);
-      *reinterpret_cast<ushort4 *>(g.h_frag + slot * 8 + (o & 7)) = hv;
+      store_stream(g.h_frag + slot * 8 + (o & 7), hv);
     }
   }
 }

@@ -6,6 +6,16 @@ namespace tr {
 
 enum GemmMode { GEMM_STORE = 0, GEMM_SWIGLU = 2 };
 
+// Streaming store for activations that the next kernel reads once: written through as issued, so the
+// kernel does not end with dirty L2 lines to write back before its successor may start (the consumers
+// mostly sit on other XCDs and read through memory anyway).  Measured per producer; it pays for the
+// SwiGLU output and the attention output, not for K-split partial sums or the query / key writes.
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2s;
+__device__ inline void store_stream(bf16_t *p, ushort4 v) {
+  __builtin_nontemporal_store(u32x2s{(uint32_t)v.x | ((uint32_t)v.y << 16), (uint32_t)v.z | ((uint32_t)v.w << 16)},
+                              reinterpret_cast<u32x2s *>(p));
+}
+
 // Fragment order (see tr_gemm_mfma.hip): a tile of 16 rows x 32 k is 64 lane slots of 8 bf16;
 // element (row r, k) of an operand with T row tiles lives in tile (k/32, r/16) at lane slot
 // (r%16) + 16*((k%32)/8), element k%8.  Weights use tile index (r/16) * (K/32) + k/32 instead.
