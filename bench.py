@@ -30,7 +30,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--shape", default="7b")
-    ap.add_argument("--prompt-len", type=int, default=512)
+    ap.add_argument("--prompt-len", type=int, default=0,
+                    help="0: the prompt length of the shape's workload (7b 512, 13b 2048, 70b 4096)")
     ap.add_argument("--profile-steps", type=int, default=4)
     ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--no-ar", action="store_true", help="skip the 1-node autoregressive comparison run")
@@ -140,6 +141,8 @@ def main():
     tr.lib()
     torch.cuda.set_device(0)
     sh = synth.SHAPES[a.shape]
+    if a.prompt_len <= 0:
+        a.prompt_len = {"7b": 512, "13b": 2048, "70b": 4096}.get(a.shape, 512)
     tmpl = synth.tree80()
     K = 8
     # a model too large to hold twice (row-major + packed) is generated and packed one layer at a time;

@@ -212,11 +212,15 @@ tr_status tr_plan_projection(int32_t n_rows, int32_t in_f, int32_t out_f, int32_
                              int32_t max_splits, int32_t *plan);
 
 /*
- * Key-axis splits the tree-attention kernel (Section 2.2 "Tree Attention") would use for n_heads query
- * heads and a host bound len_bound on committed length + tree nodes (diagnostic; touches no GPU).
- * splits is [host].  TR_EINVAL for null splits, n_heads < 1 or len_bound < 1.
+ * Launch plan of the tree-attention kernel (Section 2.2 "Tree Attention") for n_heads query heads over
+ * n_kv_heads K/V heads, n_nodes tree nodes and a host bound len_bound on committed length + tree nodes
+ * (diagnostic; touches no GPU): plan[0] = query heads one workgroup serves (heads sharing a K/V head
+ * share its staged tiles), plan[1] = key-axis splits.  plan is [host], 2 values.  TR_EINVAL for null
+ * plan, n_kv_heads < 1, n_heads not a positive multiple of n_kv_heads, n_nodes outside 1..TR_MAX_NODES
+ * or len_bound < 1.
  */
-tr_status tr_plan_attention(int32_t n_heads, int32_t len_bound, int32_t *splits);
+tr_status tr_plan_attention(int32_t n_heads, int32_t n_kv_heads, int32_t n_nodes, int32_t len_bound,
+                            int32_t *plan);
 
 /* Bytes of [device] workspace tr_verify_forward / tr_prefill need for this model (256-aligned). */
 tr_status tr_workspace_bytes(const tr_ctx *ctx, const tr_model *model, size_t *bytes);

@@ -210,9 +210,12 @@ tr_status tr_plan_projection(int32_t n_rows, int32_t in_f, int32_t out_f, int32_
   return TR_OK;
 }
 
-tr_status tr_plan_attention(int32_t n_heads, int32_t len_bound, int32_t *splits) {
-  if (splits == nullptr || n_heads < 1 || len_bound < 1) return TR_EINVAL;
-  *splits = attn_choose_splits(n_heads, len_bound);
+tr_status tr_plan_attention(int32_t n_heads, int32_t n_kv_heads, int32_t n_nodes, int32_t len_bound, int32_t *plan) {
+  if (plan == nullptr || n_kv_heads < 1 || n_heads < n_kv_heads || n_heads % n_kv_heads != 0 || n_nodes < 1 ||
+      n_nodes > TR_MAX_NODES || len_bound < 1)
+    return TR_EINVAL;
+  plan[0] = attn_heads_per_wg(n_heads, n_kv_heads, n_nodes);
+  plan[1] = attn_choose_splits(n_heads / plan[0], len_bound);
   return TR_OK;
 }
 

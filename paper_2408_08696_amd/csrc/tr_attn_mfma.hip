@@ -1,9 +1,13 @@
 // Tree attention on the matrix cores (Section 2.2 "Tree Attention"): head_dim 128, bf16 Q/K/V, float32
 // softmax statistics and accumulators.  HBM-bound: every K/V byte of the head is read once per call.
 //
-// Grid (head, split): a workgroup owns one query head and one contiguous range of 32-key tiles; its waves
-// own one tile of 16 tree nodes each, so no cross-wave reduction is needed.  K and V tiles are staged
-// through LDS (double buffered, one barrier per tile) and shared by the waves.
+// A workgroup owns HPW query heads that share one K/V head (HPW = 2 under grouped-query attention with an
+// even group, else 1) and every nsplit-th 32-key tile; its waves own one (head, tile of 16 tree nodes)
+// each, so no cross-wave reduction is needed.  K and V tiles are staged through LDS (double buffered,
+// one barrier per tile) and shared by the waves, so two heads of a group read their K/V once instead of
+// twice.  The grid is (K/V head, head group, split): workgroups that read the same K/V head have linear
+// ids congruent modulo the number of K/V heads and, with 8 of those and round-robin dispatch, land on one
+// XCD, whose L2 then serves the remaining re-reads.
 //
 // Everything is computed transposed so that no value ever changes lanes between the two contractions:
 //   S^T[key][node] = K[key][:] . Q[node][:]      A = K tile (16 keys x 32 d), B = Q^T; lane l receives
@@ -36,27 +40,32 @@ __device__ inline f32x4 mfma16a(const u32x4 &a, const u32x4 &b, f32x4 c) {
 constexpr int ATT_TILE_BYTES = 16384; // 32 keys: K 8 KiB + V 8 KiB
 constexpr float NEG_BIG = -1e30f;
 
-template <int NT>
-__global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict__ q, const bf16_t *__restrict__ Kl,
+template <int NT, int HPW>
+__global__ __launch_bounds__(NT * HPW * 64) void k_attn_mfma(const bf16_t *__restrict__ q, const bf16_t *__restrict__ Kl,
                                                        const bf16_t *__restrict__ Vl, int32_t H, int32_t Hkv,
                                                        int32_t cap, int32_t n, const uint64_t *__restrict__ anc,
                                                        const int32_t *__restrict__ d_len, int32_t nsplit,
                                                        float *__restrict__ part_ml, float *__restrict__ part_acc,
                                                        bf16_t *__restrict__ out, int32_t out_row_tiles) {
-  constexpr int THREADS = NT * 64;
+  constexpr int THREADS = NT * HPW * 64;
   constexpr int SLOTS = ATT_TILE_BYTES / 16;                 // 16-byte slots per tile
   constexpr int PER_THREAD = (SLOTS + THREADS - 1) / THREADS;
-  __shared__ u32x4 lds[2][SLOTS];
+  // two tile buffers; reused at the end for one 4 KiB block per wave
+  constexpr int LDS_SLOTS = 2 * SLOTS > NT * HPW * 256 ? 2 * SLOTS : NT * HPW * 256;
+  __shared__ u32x4 lds_all[LDS_SLOTS];
+  u32x4 (*lds)[SLOTS] = reinterpret_cast<u32x4 (*)[SLOTS]>(lds_all);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r = lane & 15, g = lane >> 4;
-  const int h = blockIdx.x, split = blockIdx.y;
-  const int hk = h / (H / Hkv);
+  const int wt = wave % NT;                                  // node tile of this wave
+  // grid (K/V head, head group inside it, split): linear ids of one K/V head differ by multiples of Hkv
+  const int hk = blockIdx.x, split = blockIdx.z;
+  const int h = hk * (H / Hkv) + blockIdx.y * HPW + wave / NT;
   // split s owns tiles s, s + nsplit, s + 2 nsplit, ...: its first tile does not depend on the committed
   // length, so that fetch is issued before the length has arrived, and the masked tiles at the end of
   // the sequence spread over the splits
 
-  const int node = wave * 16 + r;
+  const int node = wt * 16 + r;
   const int node_c = node < n ? node : n - 1;
   // Q^T operand: lane (node r, group g) holds Q[node][32c + 8g .. +7] for d-step c
   u32x4 qf[4];
@@ -80,6 +89,10 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
   float m = NEG_BIG;
   const float sc = 0.08838834764831845f * 1.4426950408889634f; // 1/sqrt(128) * log2(e)
 
+  // K/V tiles travel global -> registers -> LDS with one tile of loads in flight.  More were measured and
+  // are no faster: with one query head per K/V head the workgroups together already pull K/V at the HBM
+  // rate, with shared K/V heads the per-tile chain of dependent steps (stage, barrier, score
+  // contraction, softmax, value contraction) is the limit.
   u32x4 stage[PER_THREAD];
   auto fetch = [&](int tile) {
     // K tile: 512 slots at Kh + tile*512; V tile: 512 slots at Vh + tile*512
@@ -202,7 +215,7 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
   // a split's partial result is its own normalised output (a convex combination of V rows, so it fits
   // half precision with 2^-11 relative error, below the bf16 rounding of the merged output) plus (m, l).
   // The wave's 16 x 128 block is turned through LDS so that a node's 256 bytes leave as whole lines.
-  const size_t row0 = ((size_t)split * H + h) * NP + wave * 16;
+  const size_t row0 = ((size_t)split * H + h) * NP + wt * 16;
   if (g == 0 && node < n) {
     part_ml[(row0 + r) * 2] = m;
     part_ml[(row0 + r) * 2 + 1] = lsum;
@@ -210,7 +223,7 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
   const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
   __syncthreads(); // every wave is done with the last K/V tile
   // row r keeps its 16-byte chunk c at slot c ^ r, so the 16 rows of one store hit distinct banks
-  char *blk = reinterpret_cast<char *>(&lds[0][0]) + wave * 4096;
+  char *blk = reinterpret_cast<char *>(lds_all) + wave * 4096;
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt)
     *reinterpret_cast<f16x4 *>(blk + r * 256 + (((2 * dt + (g >> 1)) ^ r) << 4) + 8 * (g & 1)) =
@@ -222,7 +235,7 @@ __global__ __launch_bounds__(NT * 64) void k_attn_mfma(const bf16_t *__restrict_
   for (int i = 0; i < 4; ++i) {
     const int c = i * 64 + lane, rr = c >> 4, cc = c & 15;
     const u32x4 v = *reinterpret_cast<const u32x4 *>(blk + rr * 256 + ((cc ^ rr) << 4));
-    if (wave * 16 + rr < n) pa[(row0 + rr) * 16 + cc] = v; // plain store: the merge pass finds these in L2
+    if (wt * 16 + rr < n) pa[(row0 + rr) * 16 + cc] = v; // plain store: the merge pass finds these in L2
   }
 }
 
@@ -270,36 +283,55 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
 
 bool attn_mfma_supported(int32_t hd, int32_t n) { return hd == 128 && n >= 1 && n <= TR_MAX_NODES; }
 
-int attn_choose_splits(int32_t H, int32_t len_bound) {
+int attn_heads_per_wg(int32_t H, int32_t Hkv, int32_t n) {
+  const int G = H / Hkv, NT = (n + 15) / 16;
+  return (G % 2 == 0 && NT * 2 <= 12) ? 2 : 1; // up to 12 waves keep 3 per SIMD and the registers they need
+}
+
+int attn_choose_splits(int32_t head_groups, int32_t len_bound) {
   const int tiles = (len_bound + 31) / 32;
   int s = 1;
-  while (s < ATTN_MAX_SPLITS && H * s < 256 && 2 * s <= tiles) s *= 2;
+  while (s < ATTN_MAX_SPLITS && head_groups * s < 256 && 2 * s <= tiles) s *= 2;
   return s;
 }
 
-template <int NT>
-static hipError_t launch_attn_nt(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
-                                 int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t nsplit, float *part_ml,
-                                 float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st) {
-  hipLaunchKernelGGL(k_attn_mfma<NT>, dim3(H, nsplit), dim3(NT * 64), 0, st, q, Kl, Vl, H, Hkv, cap, n, anc, d_len,
-                     nsplit, part_ml, part_acc, out, out_row_tiles);
+template <int NT, int HPW>
+static hipError_t launch_attn_k(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
+                                int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t nsplit, float *part_ml,
+                                float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st) {
+  hipLaunchKernelGGL((k_attn_mfma<NT, HPW>), dim3(Hkv, H / Hkv / HPW, nsplit), dim3(NT * HPW * 64), 0, st, q, Kl, Vl, H, Hkv, cap,
+                     n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles);
   return hipGetLastError();
+}
+
+template <int NT>
+static hipError_t launch_attn_nt(int hpw, const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv,
+                                 int32_t cap, int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t nsplit,
+                                 float *part_ml, float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st) {
+  if constexpr (NT <= 6) {
+    if (hpw == 2)
+      return launch_attn_k<NT, 2>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st);
+  }
+  if (hpw != 1) return hipErrorInvalidValue;
+  return launch_attn_k<NT, 1>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st);
 }
 
 hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                             int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t len_bound, float *part_ml,
                             float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st) {
-  const int nsplit = attn_choose_splits(H, len_bound);
+  if (Hkv < 1 || H % Hkv != 0) return hipErrorInvalidValue;
+  const int hpw = attn_heads_per_wg(H, Hkv, n);
+  const int nsplit = attn_choose_splits(H / hpw, len_bound);
   hipError_t e = hipErrorInvalidValue;
   switch ((n + 15) / 16) {
-  case 1: e = launch_attn_nt<1>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 2: e = launch_attn_nt<2>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 3: e = launch_attn_nt<3>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 4: e = launch_attn_nt<4>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 5: e = launch_attn_nt<5>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 6: e = launch_attn_nt<6>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 7: e = launch_attn_nt<7>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 8: e = launch_attn_nt<8>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 1: e = launch_attn_nt<1>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 2: e = launch_attn_nt<2>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 3: e = launch_attn_nt<3>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 4: e = launch_attn_nt<4>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 5: e = launch_attn_nt<5>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 6: e = launch_attn_nt<6>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 7: e = launch_attn_nt<7>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 8: e = launch_attn_nt<8>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
   }
   if (e != hipSuccess || nsplit == 1) return e;
   hipLaunchKernelGGL(k_attn_merge, dim3((n + 7) / 8, H), dim3(256), 0, st, part_ml, part_acc, H, n, nsplit, out,

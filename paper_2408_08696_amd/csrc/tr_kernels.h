@@ -89,8 +89,10 @@ hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t
 // Tree attention for head_dim 128, bf16 K/V/Q, split over the key axis with a merge pass.
 // len_bound: host upper bound of L + n (sizes the split count only).
 bool attn_mfma_supported(int32_t hd, int32_t n);
-// Key-axis splits launch_attn_mfma uses for H heads and this bound on committed length + nodes.
-int attn_choose_splits(int32_t H, int32_t len_bound);
+// Query heads one workgroup of launch_attn_mfma serves (they share a K/V head), and the key-axis splits it
+// uses for H / that many head groups and this bound on committed length + nodes.
+int attn_heads_per_wg(int32_t H, int32_t Hkv, int32_t n);
+int attn_choose_splits(int32_t head_groups, int32_t len_bound);
 hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                             int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t len_bound, float *part_ml,
                             float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st);

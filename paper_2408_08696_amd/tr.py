@@ -69,7 +69,7 @@ _SIGS = {
     "tr_build_tree": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "tr_workspace_bytes": [C.c_void_p, C.POINTER(Model), C.POINTER(C.c_size_t)],
     "tr_plan_projection": [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)],
-    "tr_plan_attention": [C.c_int32, C.c_int32, C.POINTER(C.c_int32)],
+    "tr_plan_attention": [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)],
     "tr_verify_forward": [C.c_void_p, C.POINTER(Model), C.POINTER(KV), C.c_void_p, C.c_void_p,
                           C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
     "tr_accept_and_update": [C.c_void_p, C.POINTER(KV), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -248,11 +248,11 @@ def plan_projection(n_rows: int, in_f: int, out_f: int, fused_pair: bool = False
     return tuple(plan)
 
 
-def plan_attention(n_heads: int, len_bound: int) -> int:
-    """Key-axis splits of one tree-attention launch."""
-    s = C.c_int32()
-    _check(lib().tr_plan_attention(n_heads, len_bound, C.byref(s)), "tr_plan_attention")
-    return s.value
+def plan_attention(n_heads: int, n_kv_heads: int, n_nodes: int, len_bound: int):
+    """(query heads per workgroup, key-axis splits) of one tree-attention launch."""
+    plan = (C.c_int32 * 2)()
+    _check(lib().tr_plan_attention(n_heads, n_kv_heads, n_nodes, len_bound, plan), "tr_plan_attention")
+    return tuple(plan)
 
 
 def op_stream(src, dst=None) -> None:

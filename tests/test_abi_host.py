@@ -131,16 +131,26 @@ def test_projection_plans_of_the_7b_step_fill_the_chip(lib):
 
 
 def test_attention_plan(lib):
-    s = C.c_int32()
-    assert lib.tr_plan_attention(32, 600, None) == tr.TR_EINVAL
-    assert lib.tr_plan_attention(0, 600, C.byref(s)) == tr.TR_EINVAL
-    assert lib.tr_plan_attention(32, 0, C.byref(s)) == tr.TR_EINVAL
-    for H in (1, 8, 32, 40, 64, 256):
-        prev = 1
-        for L in (1, 31, 32, 33, 64, 100, 600, 2048, 8192, 65536):
-            n = tr.plan_attention(H, L)
-            assert n >= 1 and n & (n - 1) == 0 and n <= 16
-            assert n == 1 or 2 * (n // 2) <= -(-L // 32)    # every split owns at least one 32-key tile
-            assert n == 1 or H * (n // 2) < 256              # splitting stops once the chip is full
-            assert n >= prev                                 # never fewer splits for a longer context
-            prev = n
+    plan = (C.c_int32 * 2)()
+    assert lib.tr_plan_attention(32, 32, 80, 600, None) == tr.TR_EINVAL
+    assert lib.tr_plan_attention(0, 1, 80, 600, plan) == tr.TR_EINVAL
+    assert lib.tr_plan_attention(32, 0, 80, 600, plan) == tr.TR_EINVAL
+    assert lib.tr_plan_attention(32, 5, 80, 600, plan) == tr.TR_EINVAL      # not a multiple
+    assert lib.tr_plan_attention(32, 32, 0, 600, plan) == tr.TR_EINVAL
+    assert lib.tr_plan_attention(32, 32, 129, 600, plan) == tr.TR_EINVAL
+    assert lib.tr_plan_attention(32, 32, 80, 0, plan) == tr.TR_EINVAL
+    for H, Hkv in ((1, 1), (8, 8), (32, 32), (40, 40), (64, 8), (32, 8), (4, 2), (12, 4), (256, 256)):
+        for n in (1, 16, 80, 128):
+            prev = 1
+            for L in (1, 31, 32, 33, 64, 100, 600, 2048, 8192, 65536):
+                hpw, ns = tr.plan_attention(H, Hkv, n, L)
+                assert hpw in (1, 2) and (H // Hkv) % hpw == 0       # heads of one workgroup share a K/V head
+                assert ((n + 15) // 16) * hpw <= (12 if hpw == 2 else 8)   # one wave per (head, node tile)
+                groups = H // hpw
+                assert ns >= 1 and ns & (ns - 1) == 0 and ns <= 16
+                assert ns == 1 or 2 * (ns // 2) <= -(-L // 32)        # every split owns at least one 32-key tile
+                assert ns == 1 or groups * (ns // 2) < 256            # splitting stops once the chip is full
+                assert ns >= prev                                     # never fewer splits for a longer context
+                prev = ns
+    assert tr.plan_attention(32, 32, 80, 600) == (1, 8)
+    assert tr.plan_attention(64, 8, 80, 4176)[0] == 2
