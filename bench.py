@@ -41,6 +41,10 @@ def parse():
     ap.add_argument("--sweep-nodes", default="",
                     help="comma-separated tree sizes: time the step for each (breadth-first prefixes of the 128-node "
                          "template) instead of the headline run, and print one JSON line with the table")
+    ap.add_argument("--sweep-attention", default="",
+                    help="comma-separated prefix lengths: time the tree-attention op alone (attention kernel + split "
+                         "merge, the shape's heads, 80-node tree, rotating cache layers) at each, instead of the "
+                         "headline run, and print one JSON line with the table (no model is built)")
     return ap.parse_args()
 
 
@@ -145,6 +149,22 @@ def main():
         a.prompt_len = {"7b": 512, "13b": 2048, "70b": 4096}.get(a.shape, 512)
     tmpl = synth.tree80()
     K = 8
+    if a.sweep_attention:
+        rows = []
+        for L in [int(v) for v in a.sweep_attention.split(",")]:
+            r = attention_microbench(sh, tmpl, torch, tr, L=L, reps=3)
+            r["prefix_len"] = L
+            r["plan"] = dict(zip(("heads_per_workgroup", "key_splits"),
+                                 tr.plan_attention(sh.n_heads, sh.n_kv_heads, tmpl.n_nodes, L + tmpl.n_nodes)))
+            rows.append(r)
+            say(f"L={L}: {r['us_per_layer']:.2f} us per layer")
+        print(json.dumps({"metric": "tree attention time vs prefix length", "unit": "us/layer", "n_gpus": 1,
+                          "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": f"{sh.name}-shape heads (H={sh.n_heads}, Hkv={sh.n_kv_heads}, hd="
+                                                 f"{sh.head_dim}), 80-node tree, N(0,1) Q/K/V, one launch per cache "
+                                                 f"layer over {sh.n_layers} layers"},
+                          "sweep": rows}))
+        return
     # a model too large to hold twice (row-major + packed) is generated and packed one layer at a time;
     # the row-major originals are then gone, so the oracle baseline (which needs them) is skipped
     streaming_build = sh.weight_params() * 2 * 2 > 200e9
