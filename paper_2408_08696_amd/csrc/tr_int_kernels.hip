@@ -92,27 +92,60 @@ __global__ __launch_bounds__(TOPK_THREADS) void k_topk(const T *__restrict__ log
   }
 }
 
-// Two-stage variant for k <= 8.  Stage 1, grid (row, segment): the row is cut into TOPK_SEGS segments;
-// every thread loads its (at most TOPK_PER_THREAD) elements of the segment at once, keeps them sorted in
-// registers, and k rounds of a workgroup-wide "best head of list" write the segment's k best candidates.
-// Stage 2, one wave per row: the TOPK_SEGS * k candidates are merged the same way.  Both stages use the
-// total order of k_topk, so ties resolve identically.
-constexpr int TOPK_SEGS = 8;
+// Two-stage variant for k <= 8, without workgroup barriers.  An element becomes one 64-bit key whose
+// unsigned order is the total order of k_topk: the float mapped to an order-preserving unsigned (with
+// -0 folded onto +0) in the high word, the complemented index in the low word; key 0 is "nothing".
+// Stage 1: every wave owns TOPK_WAVE_ELEMS consecutive elements of a row, each lane holds 16 of them in
+// registers together with their maximum, and k rounds of "wave-wide maximum, the owning lane drops it and
+// recomputes its own" write the wave's k best keys.  Stage 2, one wave per row, merges the candidates of
+// all waves of the row the same way (up to 16 per lane).
+constexpr int TOPK_EPL = 16;                     // elements per lane
+constexpr int TOPK_WAVE_ELEMS = 64 * TOPK_EPL;   // elements per stage-1 wave
 constexpr int TOPK1_THREADS = 256;
-constexpr int TOPK_PER_THREAD = 8; // registers per thread; longer segments loop
+constexpr int TOPK_MAX_WAVES_PER_ROW = 128;      // stage 2 holds 8 candidates per wave, 16 per lane
 
-__device__ inline void insert8(Cand (&l)[8], const Cand &e) {
-  if (before(e, l[7])) {
-    bool placed = false;
+__device__ inline uint64_t topk_key(float v, int32_t idx) {
+  uint32_t u = __float_as_uint(v + 0.0f); // -0 + 0 = +0
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ((uint64_t)u << 32) | (uint32_t)~idx;
+}
+// Wave-wide maximum on the vector ALU alone: four data-parallel-primitive exchanges (lane ^ 1, lane ^ 2,
+// mirror inside 8 lanes, mirror inside the row of 16) leave every lane with its row's maximum, and the
+// four row maxima are read out as scalars.  All 64 lanes must be active.
+template <int CTRL>
+__device__ inline uint64_t dpp_u64(uint64_t x) {
+  const uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
+  const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, 0xF, 0xF, false);
+  const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)hi, CTRL, 0xF, 0xF, false);
+  return ((uint64_t)h2 << 32) | l2;
+}
+__device__ inline uint64_t readlane_u64(uint64_t x, int lane) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), lane);
+  return ((uint64_t)hi << 32) | lo;
+}
+__device__ inline uint64_t max_u64(uint64_t a, uint64_t b) { return a > b ? a : b; }
+__device__ inline uint64_t wave_max_u64(uint64_t x) {
+  x = max_u64(x, dpp_u64<0xB1>(x));  // quad_perm [1,0,3,2]
+  x = max_u64(x, dpp_u64<0x4E>(x));  // quad_perm [2,3,0,1]
+  x = max_u64(x, dpp_u64<0x141>(x)); // row_half_mirror
+  x = max_u64(x, dpp_u64<0x140>(x)); // row_mirror
+  return max_u64(max_u64(readlane_u64(x, 0), readlane_u64(x, 16)), max_u64(readlane_u64(x, 32), readlane_u64(x, 48)));
+}
+// k rounds of maximum-with-replacement over the keys every lane holds; lane 0 writes the winners
+__device__ inline void wave_select(uint64_t (&key)[TOPK_EPL], int32_t k, uint64_t *__restrict__ out) {
+  uint64_t m = 0;
 #pragma unroll
-    for (int p = 7; p >= 0; --p) {
-      if (!placed) {
-        if (p > 0 && before(e, l[p - 1])) {
-          l[p] = l[p - 1];
-        } else {
-          l[p] = e;
-          placed = true;
-        }
+  for (int b = 0; b < TOPK_EPL; ++b) m = key[b] > m ? key[b] : m;
+  for (int p = 0; p < k; ++p) {
+    const uint64_t best = wave_max_u64(m);
+    if ((threadIdx.x & 63) == 0) out[p] = best;
+    if (m == best && best != 0) { // keys are unique (the index is part of them): one lane owns the winner
+      m = 0;
+#pragma unroll
+      for (int b = 0; b < TOPK_EPL; ++b) {
+        if (key[b] == best) key[b] = 0;
+        m = key[b] > m ? key[b] : m;
       }
     }
   }
@@ -120,99 +153,55 @@ __device__ inline void insert8(Cand (&l)[8], const Cand &e) {
 
 template <typename T>
 __global__ __launch_bounds__(TOPK1_THREADS) void k_topk_stage1(const T *__restrict__ logits, int32_t V, int32_t k,
-                                                                Cand *__restrict__ cand) {
-  __shared__ Cand red[TOPK1_THREADS / 64];
-  const int rowi = blockIdx.x, seg = blockIdx.y, tid = threadIdx.x;
+                                                                int32_t waves_per_row, uint64_t *__restrict__ cand) {
+  const int rowi = blockIdx.y, lane = threadIdx.x & 63;
+  const int w = blockIdx.x * (TOPK1_THREADS / 64) + (threadIdx.x >> 6); // wave index inside the row
+  if (w >= waves_per_row) return;
   const T *row = logits + (size_t)rowi * V;
-  const int seg_len = (V + TOPK_SEGS - 1) / TOPK_SEGS;
-  const int lo = seg * seg_len;
-  const int hi = lo + seg_len < V ? lo + seg_len : V;
-  Cand l[8];
+  const int lo = w * TOPK_WAVE_ELEMS;
+  uint64_t key[TOPK_EPL];
 #pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    l[p].v = -__builtin_inff();
-    l[p].i = 0x7FFFFFFF; // sentinel: after every real element
+  for (int b = 0; b < TOPK_EPL; ++b) {
+    const int j = lo + b * 64 + lane;
+    key[b] = j < V ? topk_key(to_f32<T>(row[j]), j) : 0;
   }
-  for (int j0 = lo + tid; j0 < hi; j0 += TOPK_PER_THREAD * TOPK1_THREADS) {
-    float batch[TOPK_PER_THREAD];
-#pragma unroll
-    for (int b = 0; b < TOPK_PER_THREAD; ++b) {
-      const int j = j0 + b * TOPK1_THREADS;
-      batch[b] = j < hi ? to_f32<T>(row[j]) : -__builtin_inff();
-    }
-#pragma unroll
-    for (int b = 0; b < TOPK_PER_THREAD; ++b) {
-      Cand e;
-      e.v = batch[b];
-      e.i = j0 + b * TOPK1_THREADS;
-      if (e.i < hi) insert8(l, e);
-    }
-  }
-  for (int p = 0; p < k; ++p) {
-    Cand best = l[0];
-    for (int off = 32; off > 0; off >>= 1) {
-      Cand o;
-      o.v = __shfl_xor(best.v, off);
-      o.i = __shfl_xor(best.i, off);
-      if (before(o, best)) best = o;
-    }
-    if ((tid & 63) == 0) red[tid >> 6] = best;
-    __syncthreads();
-    Cand b = red[0];
-#pragma unroll
-    for (int w = 1; w < TOPK1_THREADS / 64; ++w)
-      if (before(red[w], b)) b = red[w];
-    if (tid == 0) cand[((size_t)rowi * TOPK_SEGS + seg) * 8 + p] = b;
-    // the owner of the winning element pops it (real indices are unique; sentinels never need popping)
-    if (l[0].i == b.i && b.i != 0x7FFFFFFF) {
-#pragma unroll
-      for (int q = 0; q < 7; ++q) l[q] = l[q + 1];
-      l[7].v = -__builtin_inff();
-      l[7].i = 0x7FFFFFFF;
-    }
-    __syncthreads();
-  }
+  wave_select(key, k, cand + ((size_t)rowi * waves_per_row + w) * 8);
 }
 
-__global__ __launch_bounds__(64) void k_topk_stage2(const Cand *__restrict__ cand, int32_t k, int32_t *__restrict__ out) {
+__global__ __launch_bounds__(64) void k_topk_stage2(const uint64_t *__restrict__ cand, int32_t k, int32_t waves_per_row,
+                                                    int32_t *__restrict__ out) {
   const int rowi = blockIdx.x, lane = threadIdx.x;
-  // lane = segment * 8 + rank; ranks >= k were not written by stage 1
-  Cand mine = cand[(size_t)rowi * TOPK_SEGS * 8 + lane];
-  if ((lane & 7) >= k) {
-    mine.v = -__builtin_inff();
-    mine.i = 0x7FFFFFFF;
+  const int n_cand = waves_per_row * 8; // slot c: wave c / 8, rank c % 8; ranks >= k were not written
+  uint64_t key[TOPK_EPL];
+#pragma unroll
+  for (int b = 0; b < TOPK_EPL; ++b) {
+    const int c = b * 64 + lane;
+    key[b] = (c < n_cand && (c & 7) < k) ? cand[(size_t)rowi * n_cand + c] : 0;
   }
-  for (int p = 0; p < k; ++p) {
-    Cand best = mine;
-    for (int off = 32; off > 0; off >>= 1) {
-      Cand o;
-      o.v = __shfl_xor(best.v, off);
-      o.i = __shfl_xor(best.i, off);
-      if (before(o, best)) best = o;
-    }
-    if (lane == 0) out[(size_t)rowi * k + p] = best.i;
-    if (mine.i == best.i) {
-      mine.v = -__builtin_inff();
-      mine.i = 0x7FFFFFFF;
-    }
-  }
+  __shared__ uint64_t win[8];
+  wave_select(key, k, win);
+  __syncthreads();
+  if (lane < k) out[(size_t)rowi * k + lane] = (int32_t)~(uint32_t)win[lane];
 }
 
 hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k, int32_t *d_topk,
                        void *d_cand, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
   const size_t esz = dtype_size(dtype);
-  if (k <= 8 && V >= TOPK_SEGS * k && d_cand != nullptr) {
+  const int wpr = (V + TOPK_WAVE_ELEMS - 1) / TOPK_WAVE_ELEMS;
+  if (k <= 8 && V >= 8 && wpr <= TOPK_MAX_WAVES_PER_ROW && d_cand != nullptr) {
+    const int wg_per_row = (wpr + TOPK1_THREADS / 64 - 1) / (TOPK1_THREADS / 64);
     for (int r0 = 0; r0 < rows; r0 += TR_MAX_NODES) { // the candidate scratch holds TR_MAX_NODES rows
       const int nr = rows - r0 < TR_MAX_NODES ? rows - r0 : TR_MAX_NODES;
       const char *src = (const char *)logits + (size_t)r0 * V * esz;
       if (dtype == TR_BF16)
-        hipLaunchKernelGGL(k_topk_stage1<bf16_t>, dim3(nr, TOPK_SEGS), dim3(TOPK1_THREADS), 0, st, (const bf16_t *)src, V,
-                           k, (Cand *)d_cand);
+        hipLaunchKernelGGL(k_topk_stage1<bf16_t>, dim3(wg_per_row, nr), dim3(TOPK1_THREADS), 0, st, (const bf16_t *)src,
+                           V, k, wpr, (uint64_t *)d_cand);
       else
-        hipLaunchKernelGGL(k_topk_stage1<float>, dim3(nr, TOPK_SEGS), dim3(TOPK1_THREADS), 0, st, (const float *)src, V,
-                           k, (Cand *)d_cand);
-      hipLaunchKernelGGL(k_topk_stage2, dim3(nr), dim3(64), 0, st, (const Cand *)d_cand, k, d_topk + (size_t)r0 * k);
+        hipLaunchKernelGGL(k_topk_stage1<float>, dim3(wg_per_row, nr), dim3(TOPK1_THREADS), 0, st, (const float *)src, V,
+                           k, wpr, (uint64_t *)d_cand);
+      hipLaunchKernelGGL(k_topk_stage2, dim3(nr), dim3(64), 0, st, (const uint64_t *)d_cand, k, wpr,
+                         d_topk + (size_t)r0 * k);
     }
     return hipGetLastError();
   }
@@ -223,7 +212,7 @@ hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t 
   return hipGetLastError();
 }
 
-size_t topk_scratch_bytes() { return (size_t)TR_MAX_NODES * TOPK_SEGS * 8 * sizeof(Cand); }
+size_t topk_scratch_bytes() { return (size_t)TR_MAX_NODES * TOPK_MAX_WAVES_PER_ROW * 8 * sizeof(uint64_t); }
 
 // ---------------------------------------------------------------------------------------------
 // Matrix update (Section 3.3): M[S[i], :] = topk[i, :] for every node.  A token that occurs more
