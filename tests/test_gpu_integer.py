@@ -90,6 +90,27 @@ def test_topk_other_k():
         ctx.close()
 
 
+@pytest.mark.parametrize("V", [8, 9, 1023, 1025, 2049, 131072, 131073, 152064])
+def test_topk_vocabulary_edges(V):
+    """Vocabularies around the kernel's units: below and above one wave's 1024 elements, the largest row
+    the two-stage path takes (128 waves) and the first sizes beyond it (one-kernel path); ties included."""
+    require_gpu()
+    rows = 5
+    say("topk edges", V)
+    x = synth.normal_tensor((rows, V), 3.0, seed=V, dtype=torch.float32)
+    x[1, :] = 1.5
+    x[2, V - 8:] = x[2].max() + 1
+    x[3, ::3] = x[3].max()
+    x[4, 0] = -0.0
+    ctx = _ctx(synth.single(), V)
+    d_topk = torch.zeros(rows, K, dtype=torch.int32, device="cuda")
+    ctx.op_topk(x.cuda(), d_topk)
+    got = d_topk.cpu().numpy()
+    for r in range(rows):
+        assert got[r].tolist() == O.topk_ids(x[r].numpy(), K).tolist(), (V, r)
+    ctx.close()
+
+
 @pytest.mark.parametrize("name", ["tree80", "wide128", "tree15"])
 def test_matrix_update_last_wins(name):
     require_gpu()
