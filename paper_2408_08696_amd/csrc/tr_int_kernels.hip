@@ -279,6 +279,11 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_accept_update(int32_t *__restr
   const int i = threadIdx.x;
   const bool live = i < t.n_nodes;
   if (i == 0) best_key = -1;
+  // everything that does not depend on the match is loaded up front, in one round trip
+  const uint64_t anc0 = live ? t.anc[2 * i] : 0, anc1 = live ? t.anc[2 * i + 1] : 0;
+  const int dep = live ? t.depth[i] : 0;
+  const int par = live && i > 0 ? t.parent[i] : 0;
+  const int L0 = i == 0 ? *d_len : 0;
   if (live) {
     int tk = S[i];
     sS[i] = tk < 0 ? 0 : (tk >= V ? V - 1 : tk);
@@ -287,14 +292,13 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_accept_update(int32_t *__restr
     sOut[i] = ot < 0 ? 0 : (ot >= V ? V - 1 : ot);
   }
   __syncthreads();
-  const bool match = live && (i == 0 || sS[i] == sOut[t.parent[i]]);
+  const bool match = live && (i == 0 || sS[i] == sOut[par]);
   const uint64_t ballot = __ballot(match);
   if ((i & 63) == 0) mbits[i >> 6] = ballot;
   __syncthreads();
   if (live) {
-    const uint64_t a0 = t.anc[2 * i], a1 = t.anc[2 * i + 1];
-    const bool ok = ((mbits[0] & a0) == a0) && ((mbits[1] & a1) == a1);
-    if (ok) atomicMax(&best_key, t.depth[i] * 256 + (255 - i));
+    const bool ok = ((mbits[0] & anc0) == anc0) && ((mbits[1] & anc1) == anc1);
+    if (ok) atomicMax(&best_key, dep * 256 + (255 - i));
   }
   __syncthreads();
   if (i == 0) {
@@ -321,7 +325,7 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_accept_update(int32_t *__restr
     out->n_emitted = a + 1;
     out->winner = w;
     out->next_root = bonus;
-    const int L = *d_len;
+    const int L = L0;
     *step_L = L;
     *d_len = L + a + 1;
     out->kv_len = L + a + 1;
