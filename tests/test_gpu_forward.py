@@ -198,14 +198,19 @@ def test_capacity_is_checked_on_the_host():
 @pytest.mark.parametrize("tmpl_name,H,Hkv,L,tiled", [("tree80", 32, 32, 1024, True), ("tree80", 8, 2, 1000, True),
                                                      ("tree81", 4, 4, 37, True), ("wide128", 4, 1, 300, True),
                                                      ("single", 8, 8, 513, True), ("tree15", 4, 4, 0, True),
-                                                     ("tree80", 4, 2, 200, False)])
+                                                     ("tree80", 4, 2, 200, False),
+                                                     # grouped-query shapes: the 70B head layout at its prompt
+                                                     # length (two heads per workgroup), an odd group (one head
+                                                     # per workgroup), six node tiles with shared heads, one node
+                                                     ("tree80", 64, 8, 4096, True), ("tree80", 6, 2, 150, True),
+                                                     ("prefix96", 8, 4, 70, True), ("single", 16, 2, 777, True)])
 def test_tree_attention_matches_per_path_attention(tmpl_name, H, Hkv, L, tiled):
     """One layer of tree attention at the microbenchmark shape (32 heads x 128, prefix 1024, 80
     nodes, N(0,1) values) and smaller ones: every node must equal plain softmax attention over
     (prefix, its root-to-node path) computed by the oracle in float64."""
     require_gpu()
     say("tree attention", tmpl_name, H, Hkv, L, tiled)
-    t = synth.TEMPLATES[tmpl_name]()
+    t = synth.prefix_template(int(tmpl_name[6:])) if tmpl_name.startswith("prefix") else synth.TEMPLATES[tmpl_name]()
     tree = O.make_tree(t.parent, t.rank, K)
     n, hd = t.n_nodes, 128
     sh = synth.ModelShape("att", 1, H * hd, H, Hkv, hd, 64, 64, "bf16")
