@@ -82,7 +82,21 @@ hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t
 // ---------------------------------------------------------------------------------------------
 // the GEMM
 // ---------------------------------------------------------------------------------------------
-template <int NT, int NW, int MODE, int GW>
+// LDS the tail needs: the GW partials of the tiles of one reduce-scatter pass, plus the per-row scales when
+// the epilogue applies an RMS scale.  One pass if all tiles fit the 160 KB of a CU, else two (the first
+// covers the units of waves 0 .. GW/2-1).
+constexpr size_t gemm_scale_lds_bytes(int nt, bool scaled) { return scaled ? (size_t)nt * 16 * sizeof(float) : 0; }
+constexpr bool gemm_tail_one_pass(int p, int nt, int mode, int gw, bool scaled) {
+  return (size_t)p * nt * (mode == GEMM_SWIGLU ? 2 : 1) * gw * 1024 + gemm_scale_lds_bytes(nt, scaled) <= 160 * 1024;
+}
+constexpr size_t gemm_tail_red_bytes(int p, int nt, int mode, int gw, bool scaled) {
+  const int u = p * nt, upw = (u + gw - 1) / gw;
+  const int own0 = gemm_tail_one_pass(p, nt, mode, gw, scaled) ? gw : gw / 2;
+  const int units0 = own0 * upw < u ? own0 * upw : u;
+  return (size_t)units0 * (mode == GEMM_SWIGLU ? 2 : 1) * gw * 1024;
+}
+
+template <int NT, int NW, int MODE, int GW, bool SCALED>
 __global__ __launch_bounds__(GW * 64) void k_gemm_mfma(GemmArgs g) {
   // SWIGLU: NW = 2P; weight tiles 0..P-1 come from the gate matrix, P..2P-1 from the up matrix
   constexpr int P = MODE == GEMM_SWIGLU ? NW / 2 : NW; // distinct out-tiles per workgroup
@@ -126,14 +140,14 @@ __global__ __launch_bounds__(GW * 64) void k_gemm_mfma(GemmArgs g) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // optional per-row RMS scale for the epilogue (wave 0 only).  Lane group g fetches chunks g and g+4 of
-  // its row's sums of squares now, with no dependent arithmetic, so the loads retire under the main
-  // loop; the epilogue adds the groups with two shuffles (n_ssq <= 8).
+  // per-row RMS scale for the epilogue (SCALED kernels, wave 0 only).  Lane group g fetches chunks g and g+4
+  // of its row's sums of squares now, with no dependent arithmetic, so the loads retire under the main
+  // loop; the tail adds the groups with two shuffles (n_ssq <= 8) and hands the scales out through LDS.
   float row_ss[NT][2];
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int row = 16 * t + (lane & 15), c0 = lane >> 4;
-    const bool on = wave == 0 && g.row_ssq != nullptr && row < g.n;
+    const bool on = SCALED && wave == 0 && row < g.n;
     row_ss[t][0] = on && c0 < g.n_ssq ? g.row_ssq[(size_t)row * g.n_ssq + c0] : 0.f;
     row_ss[t][1] = on && c0 + 4 < g.n_ssq ? g.row_ssq[(size_t)row * g.n_ssq + c0 + 4] : 0.f;
   }
@@ -164,23 +178,23 @@ __global__ __launch_bounds__(GW * 64) void k_gemm_mfma(GemmArgs g) {
 
   // Cross-wave reduction as a reduce-scatter through LDS, then a distributed epilogue.  The NW*NT
   // accumulator tiles form U units of TPU tiles (one tile; for SWIGLU a gate tile and its up tile); wave w
-  // owns units w*UPW .. w*UPW+UPW-1.  In each of two passes (LDS holds half of all partial tiles) every
-  // wave publishes its partial of the tiles owned by that pass's waves, and each owner adds the GW
-  // partials of its tiles in wave order (a fixed order: results are run-to-run identical).  Every wave
-  // then scales, activates and stores its own few tiles, instead of one wave storing them all.
+  // owns units w*UPW .. w*UPW+UPW-1.  Every wave publishes its partial of each tile and the owner adds the
+  // GW partials in wave order (a fixed order: results are run-to-run identical).  When the GW partials of
+  // all tiles fit LDS this is one pass; otherwise two, the first for the units of waves 0 .. GW/2-1.
+  // Every wave then scales, activates and stores its own few tiles, instead of one wave storing them all.
   constexpr int TPU = MODE == GEMM_SWIGLU ? 2 : 1;
   constexpr int U = P * NT;
   constexpr int UPW = (U + GW - 1) / GW;
-  constexpr int OWN0 = GW / 2; // waves 0 .. OWN0-1 own the units of pass 0
+  constexpr int OWN0 = gemm_tail_one_pass(P, NT, MODE, GW, SCALED) ? GW : GW / 2; // waves 0 .. OWN0-1 own pass 0
   float4 *red4 = reinterpret_cast<float4 *>(red); // [unit slot * TPU + k][GW][64]
-  float *sc_lds = red + (size_t)OWN0 * UPW * TPU * GW * 64 * 4; // [NT * 16] per-row scale
-  if (wave == 0) {
+  float *sc_lds = red + gemm_tail_red_bytes(P, NT, MODE, GW, SCALED) / sizeof(float); // [NT * 16], SCALED only
+  if (SCALED && wave == 0) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       float ss = row_ss[t][0] + row_ss[t][1];
       ss += __shfl_xor(ss, 16);
       ss += __shfl_xor(ss, 32);
-      if (lane < 16) sc_lds[16 * t + lane] = g.row_ssq != nullptr ? 1.0f / sqrtf(ss / (float)g.norm_dim + g.eps) : 1.0f;
+      if (lane < 16) sc_lds[16 * t + lane] = 1.0f / sqrtf(ss / (float)g.norm_dim + g.eps);
     }
   }
   f32x4 fin[UPW][TPU];
@@ -230,11 +244,11 @@ __global__ __launch_bounds__(GW * 64) void k_gemm_mfma(GemmArgs g) {
     const int u = id / NT, t = id - u * NT;
     if (u >= n_valid) continue;
     const int row = 16 * t + r;
-    const float sc = sc_lds[row];
+    const float sc_row = SCALED ? sc_lds[row] : 1.0f;
     const int o = (tile0 + u) * 16 + 4 * gq;
     if (MODE == GEMM_STORE) {
       if (row >= g.n) continue;
-      const f32x4 v = f32x4{fin[i][0][0] * sc, fin[i][0][1] * sc, fin[i][0][2] * sc, fin[i][0][3] * sc};
+      const f32x4 v = f32x4{fin[i][0][0] * sc_row, fin[i][0][1] * sc_row, fin[i][0][2] * sc_row, fin[i][0][3] * sc_row};
       if (g.rope.q == nullptr) {
         float *yb = g.y + (size_t)split * g.split_stride + (size_t)row * g.ldy;
         *reinterpret_cast<float4 *>(yb + o) = float4{v[0], v[1], v[2], v[3]};
@@ -273,8 +287,8 @@ __global__ __launch_bounds__(GW * 64) void k_gemm_mfma(GemmArgs g) {
       // h[row, o .. o+3] = bf16(silu(gate) * up), written in fragment order over (k = o, NT row tiles);
       // rows past n are written as zeros so the consumer's operand tiles are fully defined
       const bool live = row < g.n;
-      const f32x4 gt = f32x4{fin[i][0][0] * sc, fin[i][0][1] * sc, fin[i][0][2] * sc, fin[i][0][3] * sc};
-      const f32x4 up = f32x4{fin[i][TPU - 1][0] * sc, fin[i][TPU - 1][1] * sc, fin[i][TPU - 1][2] * sc, fin[i][TPU - 1][3] * sc};
+      const f32x4 gt = f32x4{fin[i][0][0] * sc_row, fin[i][0][1] * sc_row, fin[i][0][2] * sc_row, fin[i][0][3] * sc_row};
+      const f32x4 up = f32x4{fin[i][TPU - 1][0] * sc_row, fin[i][TPU - 1][1] * sc_row, fin[i][TPU - 1][2] * sc_row, fin[i][TPU - 1][3] * sc_row};
       ushort4 hv;
       hv.x = live ? f32_to_bf16(gt[0] / (1.0f + __expf(-gt[0])) * up[0]) : (bf16_t)0;
       hv.y = live ? f32_to_bf16(gt[1] / (1.0f + __expf(-gt[1])) * up[1]) : (bf16_t)0;
@@ -344,21 +358,26 @@ void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, bool swiglu, int32_t
   *out_splits = bs;
 }
 
-template <int NT, int P, int MODE, int GW = GEMM_WAVES>
-static hipError_t launch_k(const GemmArgs &g, hipStream_t st) {
+template <int NT, int P, int MODE, int GW, bool SCALED>
+static hipError_t launch_ks(const GemmArgs &g, hipStream_t st) {
   constexpr int NW = MODE == GEMM_SWIGLU ? 2 * P : P;
-  // partial tiles of the units owned by half of the waves, from all waves, plus the per-row scales
-  constexpr int TPU = MODE == GEMM_SWIGLU ? 2 : 1, UPW = (P * NT + GW - 1) / GW;
-  const size_t smem = (size_t)(GW / 2) * UPW * TPU * GW * 64 * 16 + NT * 16 * sizeof(float);
+  const size_t smem = gemm_tail_red_bytes(P, NT, MODE, GW, SCALED) + gemm_scale_lds_bytes(NT, SCALED);
   if (smem > 65536) {
     static bool once = [] {
-      return hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mfma<NT, NW, MODE, GW>),
+      return hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_mfma<NT, NW, MODE, GW, SCALED>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess;
     }();
     if (!once) return hipErrorInvalidValue;
   }
-  hipLaunchKernelGGL((k_gemm_mfma<NT, NW, MODE, GW>), dim3(g.groups, g.splits), dim3(GW * 64), smem, st, g);
+  hipLaunchKernelGGL((k_gemm_mfma<NT, NW, MODE, GW, SCALED>), dim3(g.groups, g.splits), dim3(GW * 64), smem, st, g);
   return hipGetLastError();
+}
+// the epilogue's RMS scale is a compile-time property: without it the tail needs no scale hand-out and
+// the whole of LDS can hold partial tiles
+template <int NT, int P, int MODE, int GW = GEMM_WAVES>
+static hipError_t launch_k(const GemmArgs &g, hipStream_t st) {
+  if (g.row_ssq != nullptr) return launch_ks<NT, P, MODE, GW, true>(g, st);
+  return launch_ks<NT, P, MODE, GW, false>(g, st);
 }
 
 template <int NT>
