@@ -259,6 +259,37 @@ def test_linear_bf16_packed_matches_oracle_matmul(n, K_, O_, splits):
     assert err < 2e-5 * np.sqrt(K_)                           # fp32 accumulation of K products of O(1/sqrt(K))
 
 
+def test_linear_packed_every_planned_variant():
+    """Every (row tiles, weight tiles per workgroup) pair the launch planner can choose over a grid of shapes,
+    with 1, 2 and 4 K-splits, is run once at the cheapest shape that selects it, against a float64 matrix
+    product."""
+    require_gpu()
+    chosen = {}
+    for n in (1, 5, 16, 17, 33, 48, 64, 65, 80, 96, 97, 112, 128):
+        for K_ in (256, 1024, 2048, 4096, 8192, 11008):
+            for O_ in (64, 256, 1024, 2048, 4096, 8192, 12288, 32000):
+                if K_ * O_ > 140e6:
+                    continue
+                for ms in (1, 2, 4):
+                    p, _, _ = tr.plan_projection(n, K_, O_, False, ms)
+                    key, cost = ((n + 15) // 16, p, ms), n * K_ * O_   # the op runs exactly ms K-splits
+                    if key not in chosen or cost < chosen[key][0]:
+                        chosen[key] = (cost, (n, K_, O_, ms))
+    assert len(chosen) >= 70, len(chosen)
+    ctx = tr.Context(16, 8, [-1], [-1], 1)
+    for key, (_, (n, K_, O_, ms)) in sorted(chosen.items()):
+        say("linear variant", key, "shape", n, K_, O_, "max splits", ms)
+        x = synth.normal_tensor((n, K_), 1.0, seed=n + K_, dtype=torch.bfloat16)
+        w = synth.uniform_tensor((O_, K_), float(np.sqrt(3.0 / K_)), seed=7, tensor_id=O_, dtype=torch.bfloat16)
+        y = torch.zeros(n, O_, dtype=torch.float32, device="cuda")
+        ws = torch.empty(((n + 15) // 16 * 16 * K_ * 2 + 512 + ms * n * O_ * 4 + 512), dtype=torch.uint8, device="cuda")
+        ctx.op_linear(x.cuda(), tr.pack_weight(w.cuda()), y, ws, packed=True, splits=ms)
+        ref = x.double().numpy() @ w.double().numpy().T
+        err = np.abs(y.cpu().numpy() - ref).max()
+        assert err < 2e-5 * np.sqrt(K_), (key, n, K_, O_, ms, err)
+    ctx.close()
+
+
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 def test_linear_generic_matches_oracle_matmul(dtype):
     require_gpu()
