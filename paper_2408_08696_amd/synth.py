@@ -55,6 +55,14 @@ SHAPES: Dict[str, ModelShape] = {
     "tiny_odd_bf16": ModelShape("tiny_odd_bf16", 2, 192, 3, 3, 64, 500, 1000, "bf16"),
     # packed projections with a head width the matrix-core attention does not take (generic attention, plain KV)
     "tiny_hd64_bf16": ModelShape("tiny_hd64_bf16", 2, 256, 4, 2, 64, 672, 2048, "bf16"),
+    # one-layer shapes with a narrow model but a wide FFN / many heads / a large vocabulary: they make the
+    # launch planner pick the projection-kernel variants the full-size models use (2, 3, 4 gate/up tile
+    # pairs, 3 and 4 Q/K/V tiles, 8 LM-head tiles per workgroup) at a size the CPU oracle runs in seconds
+    "zoo_ffn5504": ModelShape("zoo_ffn5504", 1, 256, 2, 2, 128, 5504, 2048, "bf16"),
+    "zoo_ffn11008": ModelShape("zoo_ffn11008", 1, 256, 2, 2, 128, 11008, 2048, "bf16"),
+    "zoo_ffn13824": ModelShape("zoo_ffn13824", 1, 256, 2, 2, 128, 13824, 2048, "bf16"),
+    "zoo_heads32": ModelShape("zoo_heads32", 1, 256, 32, 32, 128, 672, 32000, "bf16"),
+    "zoo_heads40": ModelShape("zoo_heads40", 1, 256, 40, 40, 128, 672, 2048, "bf16"),
     "7b": ModelShape("7b", 32, 4096, 32, 32, 128, 11008, 32000, "bf16"),
     "13b": ModelShape("13b", 40, 5120, 40, 40, 128, 13824, 32000, "bf16"),
     "70b": ModelShape("70b", 80, 8192, 64, 8, 128, 28672, 128256, "bf16"),

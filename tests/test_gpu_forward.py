@@ -67,7 +67,13 @@ def test_tiny_fp32_free_running(tmpl_name):
                                                   ("tiny_bf16", "single"), ("tiny", "tree80"),
                                                   ("tiny_odd_bf16", "tree80"), ("tiny_bf16:rowmajor", "tree15"),
                                                   ("tiny_bf16", "prefix48"), ("tiny_gqa_bf16", "prefix97"),
-                                                  ("tiny_hd64_bf16", "tree80"), ("tiny_gqa_bf16:plainkv", "tree80")])
+                                                  ("tiny_hd64_bf16", "tree80"), ("tiny_gqa_bf16:plainkv", "tree80"),
+                                                  # projection-kernel variants of the full-size models
+                                                  ("zoo_ffn5504", "tree80"), ("zoo_ffn5504", "tree81"),
+                                                  ("zoo_ffn11008", "tree80"), ("zoo_ffn11008", "wide128"),
+                                                  ("zoo_ffn11008", "single"), ("zoo_ffn13824", "tree80"),
+                                                  ("zoo_ffn13824", "prefix64"), ("zoo_heads32", "tree80"),
+                                                  ("zoo_heads40", "tree80"), ("zoo_heads32", "wide128")])
 def test_small_shapes_lockstep(shape_name, tmpl_name):
     require_gpu()
     pack, kv_tiled = None, None
