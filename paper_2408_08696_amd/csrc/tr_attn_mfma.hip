@@ -288,11 +288,14 @@ int attn_heads_per_wg(int32_t H, int32_t Hkv, int32_t n) {
   return (G % 2 == 0 && NT * 2 <= 12) ? 2 : 1; // up to 12 waves keep 3 per SIMD and the registers they need
 }
 
+// As many key-axis splits as keep the launch within one workgroup per CU (a second workgroup on a CU
+// shares that CU's memory rate and doubles the critical path), at least two 32-key tiles per split.
 int attn_choose_splits(int32_t head_groups, int32_t len_bound) {
   const int tiles = (len_bound + 31) / 32;
-  int s = 1;
-  while (s < ATTN_MAX_SPLITS && head_groups * s < 256 && 2 * s <= tiles) s *= 2;
-  return s;
+  int s = 256 / (head_groups > 0 ? head_groups : 1);
+  if (s > tiles / 2) s = tiles / 2;
+  if (s > ATTN_MAX_SPLITS) s = ATTN_MAX_SPLITS;
+  return s < 1 ? 1 : s;
 }
 
 template <int NT, int HPW>

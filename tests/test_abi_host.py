@@ -147,10 +147,11 @@ def test_attention_plan(lib):
                 assert hpw in (1, 2) and (H // Hkv) % hpw == 0       # heads of one workgroup share a K/V head
                 assert ((n + 15) // 16) * hpw <= (12 if hpw == 2 else 8)   # one wave per (head, node tile)
                 groups = H // hpw
-                assert ns >= 1 and ns & (ns - 1) == 0 and ns <= 16
-                assert ns == 1 or 2 * (ns // 2) <= -(-L // 32)        # every split owns at least one 32-key tile
-                assert ns == 1 or groups * (ns // 2) < 256            # splitting stops once the chip is full
+                assert 1 <= ns <= 16
+                assert ns == 1 or 2 * ns <= -(-L // 32)               # at least two 32-key tiles per split
+                assert ns == 1 or groups * ns <= 256                  # at most one workgroup per CU
                 assert ns >= prev                                     # never fewer splits for a longer context
                 prev = ns
     assert tr.plan_attention(32, 32, 80, 600) == (1, 8)
+    assert tr.plan_attention(40, 40, 80, 2128) == (1, 6)
     assert tr.plan_attention(64, 8, 80, 4176)[0] == 2
