@@ -311,6 +311,7 @@ static bool variant_ok(int NT, int p, bool swiglu) {
   const int wt = swiglu ? 2 * p : p;
   if (wt == 8) return NT == 4 || NT == 5;
   if (wt == 6) return true; // eight waves up to 5 row tiles, the four-wave form beyond
+  if (wt == 5) return !swiglu && NT <= 5;
   if (swiglu) return wt == 2 || wt == 4;
   return wt >= 1 && wt <= 4;
 }
@@ -325,10 +326,10 @@ void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, bool swiglu, int32_t
                  int32_t *out_groups, int32_t *out_splits) {
   const int NT = (n + 15) / 16, KT = K / 32;
   const double wmul = swiglu ? 2.0 : 1.0;
-  static const int cand[] = {1, 2, 3, 4, 6, 8};
+  static const int cand[] = {1, 2, 3, 4, 5, 6, 8};
   double best = 1e30;
   int bp = swiglu ? 1 : 1, bg = total_tiles, bs = 1;
-  for (int ci = 0; ci < 6; ++ci) {
+  for (int ci = 0; ci < 7; ++ci) {
     const int p = cand[ci];
     if (!variant_ok(NT, p, swiglu)) continue;
     for (int s = 1; s <= max_splits; s *= 2) {
@@ -407,6 +408,9 @@ static hipError_t launch_nt(const GemmArgs &g, hipStream_t st) {
     if (p == 6) return launch_k<NT, 6, GEMM_STORE>(g, st);
   } else {
     if (p == 6) return launch_k<NT, 6, GEMM_STORE, 4>(g, st);
+  }
+  if constexpr (NT <= 5) {
+    if (p == 5) return launch_k<NT, 5, GEMM_STORE>(g, st);
   }
   switch (p) {
   case 1: return launch_k<NT, 1, GEMM_STORE>(g, st);

@@ -94,6 +94,8 @@ def _variant_exists(nt, p, fused):
         return nt in (4, 5)
     if wt == 6:
         return True
+    if wt == 5:
+        return not fused and nt <= 5
     return wt in ((2, 4) if fused else (1, 2, 3, 4))
 
 
