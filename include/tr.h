@@ -151,7 +151,7 @@ typedef struct {
  * Create a context for vocabulary size V and k candidates per token with a static tree.
  * Allocates the adjacency matrix M[V, k] int32 on the current device, initialised to zero
  * (Section 3.1), and the device copy of the template (depths, ancestor bitmasks, layer
- * offsets).  Errors: TR_EINVAL (NULL, V <= 0, k <= 0 or > TR_MAX_K), TR_ETEMPLATE, TR_ENOMEM,
+ * offsets).  Errors: TR_EINVAL (NULL, V <= 0, k <= 0, k > TR_MAX_K or k > V), TR_ETEMPLATE, TR_ENOMEM,
  * TR_EHIP.  *out is set only on TR_OK and is released with tr_destroy.
  */
 tr_status tr_create(int32_t V, int32_t k, const tr_tree_template *tree, tr_ctx **out);
@@ -177,8 +177,8 @@ tr_status tr_matrix_store(tr_ctx *ctx, int32_t *h_M);
 /*
  * Draft-tree retrieval (Section 3.2, Algorithm 1): S[0] = *d_root and, layer by layer,
  * S[i] = M[S[parent[i]], rank[i]].  d_root [device] one int32 in [0, V); d_S [device] int32 [N],
- * the merged sequence in breadth-first order.  A root outside [0, V) is clamped into range by
- * the kernel (no error is reported from device code).
+ * the merged sequence in breadth-first order.  A root, or a stored candidate, outside [0, V) is
+ * clamped into range by the kernel (no error is reported from device code).
  */
 tr_status tr_build_tree(tr_ctx *ctx, const int32_t *d_root, int32_t *d_S, void *stream);
 

@@ -14,6 +14,8 @@ What follows the paper, function by function
                   duplicates resolved as in Appendix A.5 ("Last" by default)
   forward_nodes   Section 2.2 equations: node i sees P(x | s, its ancestors), i.e.
                   tree attention (Section 2.2 "Tree Attention")
+  prefill_then_forward   the same two passes with the layer loop outermost (large models
+                  whose weights are produced one layer at a time); pinned to them by equality
   tr_step / tr_generate / ar_generate   the decode loop of Sections 2.1 and 3
   sample_tokens   Section 5.3 "Temperature Sampling": the model's token at a node is
                   drawn from softmax(logits / T) instead of taken as the argmax
@@ -105,17 +107,15 @@ def make_tree(parent: Sequence[int], rank: Sequence[int], k: int) -> Tree:
 
 
 def build_tree(M: np.ndarray, tree: Tree, root: int) -> np.ndarray:
-    """Merged sequence S (Algorithm 1): layer by layer, every node takes the
-    rank[n]-th candidate stored for its parent's token."""
+    """Merged sequence S of the static draft tree (Algorithm 1).  The root holds the last
+    token; every other node holds the candidate its template entry names: column rank[n]
+    of the matrix row of its parent's token.  Nodes are numbered layer by layer, so a
+    parent is always filled before its children and one pass in index order visits the
+    layers in the order the algorithm expands them."""
     S = np.zeros(tree.n_nodes, dtype=np.int64)
     S[0] = root
-    layer = [0]
-    for d in range(1, tree.n_layers):
-        xs = {n: M[S[n]] for n in layer}                 # "get all candidates of L from M"
-        nxt = [n for n in range(tree.n_nodes) if tree.depth[n] == d]
-        for n in nxt:                                    # "extract next layer tokens with Tree"
-            S[n] = xs[int(tree.parent[n])][tree.rank[n]]
-        layer = nxt
+    for n in range(1, tree.n_nodes):
+        S[n] = M[S[tree.parent[n]], tree.rank[n]]
     return S
 
 
@@ -255,6 +255,43 @@ def _attend_batched(Q: np.ndarray, Kp: np.ndarray, Vp: np.ndarray, K: np.ndarray
     return out.reshape(N, H, hd)
 
 
+def _lin(Wm: np.ndarray, A: np.ndarray, dtype, row_independent: bool) -> np.ndarray:
+    """A W^T for W stored [out, in]; row by row when results must not depend on the batch."""
+    Wd = Wm.astype(dtype, copy=False)
+    if row_independent:
+        return np.stack([Wd @ A[n] for n in range(A.shape[0])])
+    return A @ Wd.T
+
+
+def _layer_forward(cfg: Config, lw: dict, Kp: np.ndarray, Vp: np.ndarray, X: np.ndarray,
+                   pos: Sequence[int], paths: Sequence[Sequence[int]], dtype, row_independent: bool):
+    """One decoder layer over N nodes that follow the prefix keys/values Kp, Vp [L, Hkv, hd].
+    Returns (X after the layer, the nodes' rotated keys [N, Hkv, hd], their values)."""
+    N = X.shape[0]
+    H, Hkv, hd = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+    group = H // Hkv
+    Hn = rmsnorm(X, lw["attn_norm"].astype(dtype), cfg.rms_eps)
+    Q = _lin(lw["wq"], Hn, dtype, row_independent).reshape(N, H, hd)
+    K = _lin(lw["wk"], Hn, dtype, row_independent).reshape(N, Hkv, hd)
+    V = _lin(lw["wv"], Hn, dtype, row_independent).reshape(N, Hkv, hd)
+    for n in range(N):
+        Q[n] = rope(Q[n], pos[n], cfg.rope_theta)
+        K[n] = rope(K[n], pos[n], cfg.rope_theta)
+    if row_independent:
+        A = np.empty((N, H, hd), dtype)
+        for n in range(N):
+            idx = list(paths[n])
+            A[n] = _attend(Q[n], np.concatenate([Kp, K[idx]], axis=0),
+                           np.concatenate([Vp, V[idx]], axis=0), group)
+    else:
+        A = _attend_batched(Q, Kp, Vp, K, V, paths, group)
+    X = X + _lin(lw["wo"], A.reshape(N, H * hd), dtype, row_independent)
+    Hn = rmsnorm(X, lw["ffn_norm"].astype(dtype), cfg.rms_eps)
+    X = X + _lin(lw["w_down"], silu(_lin(lw["w_gate"], Hn, dtype, row_independent)) *
+                 _lin(lw["w_up"], Hn, dtype, row_independent), dtype, row_independent)
+    return X, K, V
+
+
 def forward_nodes(cfg: Config, w: dict, kv: KVCache, tokens: Sequence[int], pos: Sequence[int],
                   paths: Sequence[Sequence[int]], dtype=np.float64, row_independent: bool = False,
                   want_logits: bool = True):
@@ -267,45 +304,57 @@ def forward_nodes(cfg: Config, w: dict, kv: KVCache, tokens: Sequence[int], pos:
     row_independent=True computes every node with vector operations only, so a node's
     result does not depend on which other nodes share the pass (same operation shapes
     as decoding that token alone)."""
-    N, L = len(tokens), kv.len
-    H, Hkv, hd = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
-    group = H // Hkv
+    L = kv.len
     X = np.stack([w["embed"][t].astype(dtype) for t in tokens])          # [N, d]
     node_k, node_v = [], []
-
-    def lin(Wm: np.ndarray, A: np.ndarray) -> np.ndarray:
-        Wd = Wm.astype(dtype, copy=False)
-        if row_independent:
-            return np.stack([Wd @ A[n] for n in range(A.shape[0])])
-        return A @ Wd.T
-
     for l in range(cfg.n_layers):
-        lw = w["layers"][l]
-        Hn = rmsnorm(X, lw["attn_norm"].astype(dtype), cfg.rms_eps)
-        Q = lin(lw["wq"], Hn).reshape(N, H, hd)
-        K = lin(lw["wk"], Hn).reshape(N, Hkv, hd)
-        V = lin(lw["wv"], Hn).reshape(N, Hkv, hd)
-        for n in range(N):
-            Q[n] = rope(Q[n], pos[n], cfg.rope_theta)
-            K[n] = rope(K[n], pos[n], cfg.rope_theta)
-        Kp = kv.k[l][:L].astype(dtype, copy=False)
-        Vp = kv.v[l][:L].astype(dtype, copy=False)
-        if row_independent:
-            A = np.empty((N, H, hd), dtype)
-            for n in range(N):
-                idx = list(paths[n])
-                A[n] = _attend(Q[n], np.concatenate([Kp, K[idx]], axis=0),
-                               np.concatenate([Vp, V[idx]], axis=0), group)
-        else:
-            A = _attend_batched(Q, Kp, Vp, K, V, paths, group)
-        X = X + lin(lw["wo"], A.reshape(N, H * hd))
-        Hn = rmsnorm(X, lw["ffn_norm"].astype(dtype), cfg.rms_eps)
-        X = X + lin(lw["w_down"], silu(lin(lw["w_gate"], Hn)) * lin(lw["w_up"], Hn))
+        X, K, V = _layer_forward(cfg, w["layers"][l], kv.k[l][:L].astype(dtype, copy=False),
+                                 kv.v[l][:L].astype(dtype, copy=False), X, pos, paths, dtype, row_independent)
         node_k.append(K)
         node_v.append(V)
     logits = None
     if want_logits:
-        logits = lin(w["lm_head"], rmsnorm(X, w["final_norm"].astype(dtype), cfg.rms_eps))
+        logits = _lin(w["lm_head"], rmsnorm(X, w["final_norm"].astype(dtype), cfg.rms_eps), dtype,
+                      row_independent)
+    return logits, node_k, node_v
+
+
+def prefill_then_forward(cfg: Config, w: dict, kv: KVCache, prompt_tokens: Sequence[int],
+                         tokens: Sequence[int], depth: Sequence[int], paths: Sequence[Sequence[int]],
+                         dtype=np.float64, chunk: int = 128):
+    """`prefill(prompt_tokens)` followed by `forward_nodes(tokens at kv.len + depth)`, with the
+    loops exchanged: layer l of a pass needs the cache of layer l only, so every pass (the
+    prompt chunks in order, then the nodes) is taken through layer l before anything enters
+    layer l + 1.  Each layer's weights are then used in one place, and w["layers"] may be any
+    object whose [l] builds layer l on demand (a model too large to hold in host memory).
+    Same arithmetic as the two calls; returns what forward_nodes returns, with the prompt
+    committed to the cache."""
+    prompt_tokens = list(prompt_tokens)
+    L0 = kv.len
+    if L0 + len(prompt_tokens) > kv.capacity:
+        raise ValueError("KV capacity exceeded")
+    chunks = [(lo, prompt_tokens[lo:lo + chunk]) for lo in range(0, len(prompt_tokens), chunk)]
+    Xs = [np.stack([w["embed"][t].astype(dtype) for t in part]) for _, part in chunks]
+    Xn = np.stack([w["embed"][t].astype(dtype) for t in tokens])
+    Ln = L0 + len(prompt_tokens)
+    node_k, node_v = [], []
+    for l in range(cfg.n_layers):
+        lw = w["layers"][l]
+        for c, (lo, part) in enumerate(chunks):
+            n, L = len(part), L0 + lo
+            Xs[c], K, V = _layer_forward(cfg, lw, kv.k[l][:L].astype(dtype, copy=False),
+                                         kv.v[l][:L].astype(dtype, copy=False), Xs[c],
+                                         [L + i for i in range(n)], [list(range(i + 1)) for i in range(n)],
+                                         dtype, False)
+            kv.k[l][L:L + n] = K
+            kv.v[l][L:L + n] = V
+        Xn, K, V = _layer_forward(cfg, lw, kv.k[l][:Ln].astype(dtype, copy=False),
+                                  kv.v[l][:Ln].astype(dtype, copy=False), Xn,
+                                  [Ln + int(d) for d in depth], paths, dtype, False)
+        node_k.append(K)
+        node_v.append(V)
+    kv.len = Ln
+    logits = _lin(w["lm_head"], rmsnorm(Xn, w["final_norm"].astype(dtype), cfg.rms_eps), dtype, False)
     return logits, node_k, node_v
 
 

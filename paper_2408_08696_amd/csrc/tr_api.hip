@@ -100,7 +100,7 @@ const char *tr_strerror(tr_status s) {
 }
 
 tr_status tr_create(int32_t V, int32_t k, const tr_tree_template *t, tr_ctx **out) {
-  if (out == nullptr || t == nullptr || V <= 0 || k <= 0 || k > TR_MAX_K) return TR_EINVAL;
+  if (out == nullptr || t == nullptr || V <= 0 || k <= 0 || k > TR_MAX_K || k > V) return TR_EINVAL;
   int32_t depth[TR_MAX_NODES];
   uint64_t anc[2 * TR_MAX_NODES];
   if (!derive_tree(t, k, depth, anc)) return TR_ETEMPLATE;
@@ -110,21 +110,25 @@ tr_status tr_create(int32_t V, int32_t k, const tr_tree_template *t, tr_ctx **ou
   memset(c, 0, sizeof(*c));
   c->V = V;
   c->k = k;
-  memcpy(c->h_depth, depth, sizeof(int32_t) * t->n_nodes);
 
-  // host image of both trees: [parent | rank | depth] int32 x n, then anc u64 x 2n; tree then chain
+  // host image of both trees and of the context's scratch.  The 64-bit parts come first so that every
+  // section is 8-byte aligned whatever the node count: anc u64 x 2(n + cn) (tree, then chain), the top-k
+  // candidate scratch (u64), then [parent | rank | depth] int32 x n of the tree and x cn of the chain, then
+  // the step's committed length.
   const int n = t->n_nodes, cn = TR_MAX_NODES;
-  const size_t ints = 3 * (size_t)(n + cn) * sizeof(int32_t);
   const size_t ancs = 2 * (size_t)(n + cn) * sizeof(uint64_t);
-  const size_t blob = ints + ancs + sizeof(int32_t) * 64 + topk_scratch_bytes();
+  const size_t cand = topk_scratch_bytes();
+  const size_t ints = 3 * (size_t)(n + cn) * sizeof(int32_t);
+  static_assert(sizeof(uint64_t) == 8, "section offsets below assume 8-byte words");
+  const size_t blob = ancs + cand + ints + sizeof(int32_t) * 64;
   unsigned char *h = new (std::nothrow) unsigned char[blob];
   if (h == nullptr) {
     delete c;
     return TR_ENOMEM;
   }
   memset(h, 0, blob);
-  int32_t *hi = reinterpret_cast<int32_t *>(h);
-  uint64_t *ha = reinterpret_cast<uint64_t *>(h + ints);
+  uint64_t *ha = reinterpret_cast<uint64_t *>(h);
+  int32_t *hi = reinterpret_cast<int32_t *>(h + ancs + cand);
   memcpy(hi, t->parent, sizeof(int32_t) * n);
   memcpy(hi + n, t->rank, sizeof(int32_t) * n);
   memcpy(hi + 2 * n, depth, sizeof(int32_t) * n);
@@ -152,13 +156,13 @@ tr_status tr_create(int32_t V, int32_t k, const tr_tree_template *t, tr_ctx **ou
     delete c;
     return st;
   }
-  unsigned char *d = static_cast<unsigned char *>(c->d_tree_blob);
-  const int32_t *di = reinterpret_cast<const int32_t *>(d);
-  const uint64_t *da = reinterpret_cast<const uint64_t *>(d + ints);
+  unsigned char *d = static_cast<unsigned char *>(c->d_tree_blob); // hipMalloc: 256-byte aligned
+  const uint64_t *da = reinterpret_cast<const uint64_t *>(d);
+  const int32_t *di = reinterpret_cast<const int32_t *>(d + ancs + cand);
   c->tree = TreeDev{n, t->n_layers, di, di + n, di + 2 * n, da};
   c->chain = TreeDev{cn, cn, di + 3 * n, di + 3 * n + cn, di + 3 * n + 2 * cn, da + 2 * n};
-  c->d_step_L = reinterpret_cast<int32_t *>(d + ints + ancs);
-  c->d_topk_cand = d + ints + ancs + sizeof(int32_t) * 64;
+  c->d_topk_cand = d + ancs;
+  c->d_step_L = reinterpret_cast<int32_t *>(d + ancs + cand + ints);
   *out = c;
   return TR_OK;
 }

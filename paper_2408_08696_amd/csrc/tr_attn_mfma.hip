@@ -225,9 +225,15 @@ __global__ __launch_bounds__(NT * HPW * 64) void k_attn_mfma(const bf16_t *__res
   // row r keeps its 16-byte chunk c at slot c ^ r, so the 16 rows of one store hit distinct banks
   char *blk = reinterpret_cast<char *>(lds_all) + wave * 4096;
 #pragma unroll
-  for (int dt = 0; dt < 8; ++dt)
+  for (int dt = 0; dt < 8; ++dt) {
+    // clamped to the half-precision range: a value-cache entry beyond +-65504 saturates instead of
+    // turning into an infinity that the merge would spread over the row
+    f32x4 o = acc[dt] * inv;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = fminf(fmaxf(o[e], -65504.0f), 65504.0f);
     *reinterpret_cast<f16x4 *>(blk + r * 256 + (((2 * dt + (g >> 1)) ^ r) << 4) + 8 * (g & 1)) =
-        __builtin_convertvector(acc[dt] * inv, f16x4);
+        __builtin_convertvector(o, f16x4);
+  }
   // the wave reads back only what it wrote itself; its LDS operations complete in order
   asm volatile("" ::: "memory");
   u32x4 *pa = reinterpret_cast<u32x4 *>(part_acc);
@@ -280,8 +286,6 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
                                        : ((size_t)node * H + h) * 128 + d;
   store_stream(out + idx, o);
 }
-
-bool attn_mfma_supported(int32_t hd, int32_t n) { return hd == 128 && n >= 1 && n <= TR_MAX_NODES; }
 
 int attn_heads_per_wg(int32_t H, int32_t Hkv, int32_t n) {
   const int G = H / Hkv, NT = (n + 15) / 16;

@@ -15,18 +15,21 @@ namespace tr {
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+static bool packed_supported(const tr_model &m);
+
 Workspace plan_workspace(const tr_model &m) {
   Workspace w;
+  const bool generic = !packed_supported(m); // the packed path keeps neither raw Q/K/V nor gate/up outputs
   const size_t esz = dtype_size(m.dtype);
   const size_t hq = (size_t)m.n_heads * m.head_dim, hk = (size_t)m.n_kv_heads * m.head_dim;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
   w.x = take((size_t)NP * m.d_model * 4);
   w.xn = take((size_t)NP * m.d_model * esz);
-  w.qkv = take((size_t)GEMM_MAX_SPLITS * NP * (hq + 2 * hk) * 4);
+  w.qkv = take(generic ? (size_t)NP * (hq + 2 * hk) * 4 : 0);
   w.q = take((size_t)NP * hq * esz);
   w.attn = take((size_t)NP * hq * esz);
-  w.gu = take((size_t)NP * 2 * m.d_ffn * 4);
+  w.gu = take(generic ? (size_t)NP * 2 * m.d_ffn * 4 : 0);
   w.h = take((size_t)NP * m.d_ffn * esz);
   w.rope = take((size_t)NP * m.head_dim * 4);
   w.logits = take((size_t)NP * m.vocab * 4);

@@ -25,7 +25,10 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_build_tree(const int32_t *__re
   }
   for (int d = 1; d < t.n_layers; ++d) {
     __syncthreads();
-    if (dep == d) s[i] = M[(size_t)s[par] * k + rk];
+    if (dep == d) { // a stored candidate outside [0, V) (a caller-made top-k buffer) is clamped like the root
+      const int tk = M[(size_t)s[par] * k + rk];
+      s[i] = tk < 0 ? 0 : (tk >= V ? V - 1 : tk);
+    }
   }
   __syncthreads();
   if (live) S[i] = s[i];

@@ -62,19 +62,11 @@ struct TreeDev {
   const uint64_t *anc;   // [n][2]
 };
 
-// Shapes of one forward pass, passed by value to launch helpers.
-struct FwdDims {
-  int32_t n;      // rows (tree nodes or prefill chunk)
-  int32_t d, H, Hkv, hd, F, V;
-  int32_t cap;    // KV capacity (positions)
-  float eps, theta;
-};
-
 // Workspace carve-up (byte offsets, all 256-aligned).  Buffers are sized for TR_MAX_NODES rows.
 struct Workspace {
   size_t x;        // float  [NP, d]            residual stream
   size_t xn;       // T      [NP, d]            normalised activations
-  size_t qkv;      // float  [NP, (H+2Hkv)*hd]
+  size_t qkv;      // float  [NP, (H+2Hkv)*hd]  (generic path only)
   size_t q;        // T      [NP, H*hd]         rotated queries
   size_t attn;     // T      [NP, H*hd]         attention output
   size_t gu;       // float  [NP, 2F]           gate | up (generic path only)
@@ -133,7 +125,6 @@ struct tr_ctx {
   int32_t *d_step_L;     // committed length at the start of the current accept/update
   void *d_topk_cand;     // per-segment top-k candidates (two-stage top-k)
   int32_t update_mode;   // tr_update_mode bits
-  int32_t h_depth[TR_MAX_NODES];
   tr::Profiler prof;
 };
 

@@ -88,7 +88,6 @@ hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t
 
 // Tree attention for head_dim 128, bf16 K/V/Q, split over the key axis with a merge pass.
 // len_bound: host upper bound of L + n (sizes the split count only).
-bool attn_mfma_supported(int32_t hd, int32_t n);
 // Query heads one workgroup of launch_attn_mfma serves (they share a K/V head), and the key-axis splits it
 // uses for H / that many head groups and this bound on committed length + nodes.
 int attn_heads_per_wg(int32_t H, int32_t Hkv, int32_t n);

@@ -189,6 +189,24 @@ def init_matrix(vocab: int, k: int) -> np.ndarray:
     return ((i + j) % vocab).astype(np.int32)
 
 
+def planted_matrix(M0: np.ndarray, seq: Sequence[int], plan: Sequence[int]) -> np.ndarray:
+    """Hot-start matrix (the paper's Section 3.1 lets the matrix carry over from earlier text) that
+    makes a decoding run accept planned numbers of drafts.  `seq` = the last prompt token followed by
+    the tokens decoding will produce; `plan` = accepted drafts wanted per step.  A step that starts at
+    seq[s] and is to accept a drafts gets M[seq[s+i], 0] = seq[s+i+1] for i < a, while the row of
+    seq[s+a] keeps its value from M0 (the chain breaks there); the next step starts at seq[s+a+1].
+    Data only: which lengths a run really accepts is for the caller to observe."""
+    M = np.array(M0, copy=True)
+    s = 0
+    for a in plan:
+        if s + a + 1 >= len(seq):
+            break
+        for i in range(a):
+            M[seq[s + i], 0] = seq[s + i + 1]
+        s += a + 1
+    return M
+
+
 def zipf_prompt(vocab: int, length: int, seed: int, ngram: int = 4, n_plants: int | None = None,
                 alpha: float = 1.1) -> np.ndarray:
     """Token ids with rank r drawn with p ~ r**-alpha (id = r - 1), plus planted repeats:

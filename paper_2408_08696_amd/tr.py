@@ -361,11 +361,13 @@ class Engine:
         self.tokens = None                              # drawn tokens per node (temperature sampling)
         self.root = self.out[3:4]                       # next_root field of tr_step_out
 
-    def prefill(self, prompt: Sequence[int]) -> None:
-        """Commit prompt[:-1]; the last prompt token becomes the first root."""
+    def prefill(self, prompt: Sequence[int], keep_cache: bool = False) -> None:
+        """Commit prompt[:-1]; the last prompt token becomes the first root.  keep_cache: append to
+        what the cache already holds instead of starting from an empty one."""
         import torch
         toks = torch.tensor(list(prompt), dtype=torch.int32, device=self.S.device)
-        self.kv.reset(0)
+        if not keep_cache:
+            self.kv.reset(0)
         if len(prompt) > 1:
             self.ctx.prefill(self.model, self.kv, toks[:-1].contiguous(), self.ws)
         self.root.copy_(toks[-1:])

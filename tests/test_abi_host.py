@@ -157,3 +157,8 @@ def test_attention_plan(lib):
     assert tr.plan_attention(32, 32, 80, 600) == (1, 8)
     assert tr.plan_attention(40, 40, 80, 2128) == (1, 6)
     assert tr.plan_attention(64, 8, 80, 4176)[0] == 2
+
+
+def test_create_rejects_more_candidates_than_tokens(lib):
+    st, _ = _create(lib, 4, 8, [-1], [-1], 1)
+    assert st == tr.TR_EINVAL

@@ -95,6 +95,54 @@ def test_small_shapes_lockstep(shape_name, tmpl_name):
     say(stats)
 
 
+HOT_PLAN = [5, 1, 0, 5, 2, 0, 1, 3]
+
+
+@pytest.mark.parametrize("shape_name,tmpl_name", [("tiny_bf16", "tree80"), ("tiny_gqa_bf16", "tree80"),
+                                                  ("zoo_heads32", "tree80"), ("tiny_gqa_bf16:plainkv", "tree80"),
+                                                  ("tiny_bf16", "wide128"), ("tiny", "tree15")])
+def test_hot_started_lockstep_accepts_drafts(shape_name, tmpl_name):
+    """Whole steps on the packed / matrix-core / tiled-cache path with drafts really accepted
+    (Section 2.2 chain rule, Section 3.3): the matrix starts with the oracle's continuation of the
+    prompt planted (Section 3.1 hot start), so steps accept 0, 1, ... depth-1 drafts, the accepted
+    rows are compacted, and the next step attends over the compacted rows.  Every step is compared
+    with the oracle, and so are the cache rows each step commits."""
+    require_gpu()
+    kv_tiled = None
+    if shape_name.endswith(":plainkv"):
+        shape_name, kv_tiled = shape_name.split(":")[0], False
+    sh = synth.SHAPES[shape_name]
+    tmpl = synth.TEMPLATES[tmpl_name]()
+    plan = [tmpl.n_layers - 1 if a == 5 else min(a, tmpl.n_layers - 1) for a in HOT_PLAN]
+    w = synth.make_weights(sh, seed=1)
+    prompt = synth.zipf_prompt(sh.vocab, 150, seed=3, ngram=8).tolist()
+    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=512, kv_tiled=kv_tiled)
+    stats, _ = lockstep(eng, sh, synth.weights_to_numpy(w), tmpl, prompt, len(plan), synth.init_matrix(sh.vocab, K),
+                        abs_tol=1e-4 if sh.dtype == "f32" else None, label=f"hot {shape_name}/{tmpl_name}",
+                        hot_plan=plan, check_cache=True)
+    say(stats)
+    seen = {s["n_emitted"] - 1 for s in stats}
+    assert {0, 1, tmpl.n_layers - 1} <= seen, seen
+
+
+def test_hot_started_sampling_lockstep():
+    """The same under temperature sampling (Section 5.3): the planted continuation is the oracle's
+    sampled one (same per-position noise), so sampled drafts are accepted and compacted."""
+    require_gpu()
+    sh = synth.SHAPES["tiny_gqa_bf16"]
+    tmpl = synth.tree80()
+    w = synth.make_weights(sh, seed=4)
+    prompt = synth.zipf_prompt(sh.vocab, 70, seed=4).tolist()
+    noise = synth.gumbel_noise(70 + (len(HOT_PLAN) + 1) * tmpl.n_layers, sh.vocab, seed=9).numpy()
+    eng = tr.Engine(sh, to_gpu(w), tmpl, k=K, capacity=70 + len(HOT_PLAN) * tmpl.n_layers + tmpl.n_nodes + 32)
+    stats, _ = lockstep(eng, sh, synth.weights_to_numpy(w), tmpl, prompt, len(HOT_PLAN),
+                        synth.init_matrix(sh.vocab, K), label="hot sampling", sampler=(1.0, noise),
+                        hot_plan=HOT_PLAN, check_cache=True)
+    say(stats)
+    seen = {s["n_emitted"] - 1 for s in stats}
+    assert {0, 1, tmpl.n_layers - 1} <= seen, seen
+
+
 @pytest.mark.parametrize("shape_name,temperature", [("tiny", 0.8), ("tiny_bf16", 0.5), ("tiny_gqa_bf16", 1.0)])
 def test_temperature_sampling_lockstep(shape_name, temperature):
     """Whole steps under temperature sampling (Section 5.3): drawn tokens, accept lengths, emitted

@@ -146,3 +146,41 @@ def test_rmsnorm_and_silu_closed_forms():
     v = np.linspace(-6, 6, 25)
     assert np.allclose(O.silu(v), torch.nn.functional.silu(torch.from_numpy(v)).numpy())
     assert O.silu(np.zeros(1))[0] == 0.0
+
+
+class _LazyLayers:
+    """w["layers"] stand-in that hands a layer out on access and counts the accesses."""
+
+    def __init__(self, layers):
+        self.layers, self.hits = layers, []
+
+    def __getitem__(self, l):
+        self.hits.append(l)
+        return self.layers[l]
+
+
+@pytest.mark.parametrize("shape", ["tiny", "tiny_gqa_bf16"])
+def test_layer_major_sweep_equals_prefill_then_forward(shape):
+    """prefill_then_forward is prefill + forward_nodes with the loops exchanged: same cache, same
+    logits, bit for bit, and every layer's weights are fetched exactly once."""
+    sh = synth.SHAPES[shape]
+    w = synth.weights_to_numpy(synth.make_weights(sh, seed=5))
+    cfg = O.Config(sh.n_layers, sh.d_model, sh.n_heads, sh.n_kv_heads, sh.head_dim, sh.d_ffn, sh.vocab)
+    t = synth.tree15()
+    tree = O.make_tree(t.parent, t.rank, 8)
+    prompt = synth.zipf_prompt(sh.vocab, 45, seed=5).tolist()
+    S = synth.random_tokens(sh.vocab, tree.n_nodes, seed=6).tolist()
+    kv_a, kv_b = O.KVCache(cfg, 96), O.KVCache(cfg, 96)
+    pre = synth.zipf_prompt(sh.vocab, 7, seed=8).tolist()     # both start from a non-empty cache
+    O.prefill(cfg, w, kv_a, pre)
+    O.prefill(cfg, w, kv_b, pre)
+    O.prefill(cfg, w, kv_a, prompt, chunk=16)
+    lo_a, k_a, v_a = O.forward_nodes(cfg, w, kv_a, S, [kv_a.len + int(d) for d in tree.depth], tree.paths)
+    lazy = dict(w, layers=_LazyLayers(w["layers"]))
+    lo_b, k_b, v_b = O.prefill_then_forward(cfg, lazy, kv_b, prompt, S, tree.depth, tree.paths, chunk=16)
+    assert lazy["layers"].hits == list(range(cfg.n_layers))
+    assert kv_a.len == kv_b.len == 7 + 45
+    assert np.array_equal(lo_a, lo_b)
+    for l in range(cfg.n_layers):
+        assert np.array_equal(kv_a.k[l], kv_b.k[l]) and np.array_equal(kv_a.v[l], kv_b.v[l])
+        assert np.array_equal(k_a[l], k_b[l]) and np.array_equal(v_a[l], v_b[l])

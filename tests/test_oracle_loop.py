@@ -116,3 +116,26 @@ def test_fixture_seed_has_no_near_ties():
     meaningful if every top-k decision is separated by far more than the fp32 kernels'
     actual logit error (~1e-6); the GPU test checks its measured error against this gap."""
     assert fixture_min_gap(0) > FIXTURE_MIN_GAP
+
+
+HOT_PLAN = [5, 1, 0, 5, 2, 0, 1, 3]
+
+
+@pytest.mark.parametrize("shape", ["tiny_bf16", "tiny_gqa_bf16"])
+def test_planted_matrix_gives_the_planned_accept_lengths(shape):
+    """Section 3.1 hot start as a test instrument: with the greedy continuation planted pair by
+    pair, the run accepts exactly the planned numbers of drafts, stays lossless, and so passes
+    through accept lengths 0, 1 and depth - 1 (what the GPU lockstep cases rely on)."""
+    sh = synth.SHAPES[shape]
+    w = synth.weights_to_numpy(synth.make_weights(sh, seed=1))
+    cfg = O.Config(sh.n_layers, sh.d_model, sh.n_heads, sh.n_kv_heads, sh.head_dim, sh.d_ffn, sh.vocab)
+    prompt = synth.zipf_prompt(sh.vocab, 150, seed=3, ngram=8).tolist()
+    n_new = sum(a + 1 for a in HOT_PLAN)
+    ar, _, _ = O.ar_generate(cfg, w, prompt, n_new)
+    t = synth.tree80()
+    tree = O.make_tree(t.parent, t.rank, K)
+    M = synth.planted_matrix(synth.init_matrix(sh.vocab, K), [prompt[-1]] + ar, HOT_PLAN).astype(np.int64)
+    toks, lens, _ = O.tr_generate(cfg, w, M, tree, prompt, n_new, K)
+    assert toks == ar
+    assert [x - 1 for x in lens] == HOT_PLAN
+    assert {0, 1, tree.n_layers - 1} <= {x - 1 for x in lens}
