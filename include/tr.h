@@ -322,6 +322,20 @@ tr_status tr_op_linear(tr_ctx *ctx, const void *d_x, const void *d_w, int32_t dt
                        void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * tr_op_topk for callers that cannot allocate device memory and therefore hold no context (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with
+ * their candidate scratch in a device array that is part of the library image (1 MiB per GPU, held
+ * until the process ends) instead of context-owned memory.  Allocates nothing, on the host or the
+ * device.  Limits: n_rows <= TR_MAX_NODES, 8 <= V <= 131072, k <= 8; beyond them TR_ECAPACITY
+ * (TR_EINVAL for NULL pointers, an unknown dtype, n_rows < 0, V <= 0, k <= 0 or k > V).  Arguments as
+ * tr_op_topk, with V and k given explicitly.  All calls on one GPU share that GPU's array: calls
+ * that overlap in time on one GPU (different streams or threads) race and must be serialised by
+ * the caller; consecutive calls on one stream are safe.
+ */
+tr_status tr_op_topk_static(const void *d_logits, int32_t dtype, int32_t n_rows, int32_t V, int32_t k,
+                            int32_t *d_topk, void *stream);
+
+/*
  * Measurement aid: one plain streaming pass over `bytes` (multiple of 16) of [device] memory with the
  * same load instructions the weight-streaming kernels use — read-only if d_dst is NULL, else a copy
  * to d_dst.  Gives the achievable HBM streaming rate on the machine at hand and a kernel of known

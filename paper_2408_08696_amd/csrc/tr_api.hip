@@ -318,6 +318,15 @@ tr_status tr_op_topk(tr_ctx *c, const void *d_logits, int32_t dtype, int32_t n_r
   return launch_topk(d_logits, dtype, n_rows, c->V, c->k, d_topk, c->d_topk_cand, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;
 }
 
+tr_status tr_op_topk_static(const void *d_logits, int32_t dtype, int32_t n_rows, int32_t V, int32_t k,
+                            int32_t *d_topk, void *stream) {
+  if (d_logits == nullptr || d_topk == nullptr || n_rows < 0) return TR_EINVAL;
+  if (dtype != TR_F32 && dtype != TR_BF16) return TR_EINVAL;
+  if (V <= 0 || k <= 0 || k > V) return TR_EINVAL;
+  if (!topk_static_fits(n_rows, V, k)) return TR_ECAPACITY;
+  return launch_topk_static(d_logits, dtype, n_rows, V, k, d_topk, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;
+}
+
 tr_status tr_op_matrix_update(tr_ctx *c, const int32_t *d_S, const int32_t *d_topk, void *stream) {
   if (c == nullptr || d_S == nullptr || d_topk == nullptr) return TR_EINVAL;
   return launch_matrix_update(c, d_S, d_topk, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;

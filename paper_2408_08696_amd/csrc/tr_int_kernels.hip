@@ -1,6 +1,8 @@
 // Integer kernels of the Token Recycling step: draft-tree gather, per-row top-k, greedy accept,
 // adjacency-matrix scatter and KV compaction.  All single-workgroup or tiny: the work is a few
 // KB of dependent L2 accesses, so each kernel is shaped to be one launch with no host round trip.
+#include <mutex>
+
 #include "tr_internal.h"
 
 namespace tr {
@@ -216,6 +218,57 @@ hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t 
 }
 
 size_t topk_scratch_bytes() { return (size_t)TR_MAX_NODES * TOPK_MAX_WAVES_PER_ROW * 8 * sizeof(uint64_t); }
+
+// ---------------------------------------------------------------------------------------------
+// argtopk without any allocation: the candidate scratch of the two-stage kernels is a file-scope device
+// array (one copy per GPU, held until the process ends) instead of memory a context allocated.  In host
+// code the array's name is only a stand-in: the address the kernels get comes from hipGetSymbolAddress,
+// asked once per device with that device current.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t TOPK_STATIC_BYTES = (size_t)TR_MAX_NODES * TOPK_MAX_WAVES_PER_ROW * 8 * sizeof(uint64_t); // 1 MiB
+static __device__ __align__(256) unsigned char scratch[TOPK_STATIC_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static void *g_scratch_ptr[MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+// Device address of this GPU's copy of `scratch`; nullptr (and *err set) if it cannot be had.
+static void *static_scratch(hipError_t *err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= MAX_DEVICES) {
+    *err = hipErrorInvalidDevice;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void *p = nullptr;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess || p == nullptr) {
+      if (*err == hipSuccess) *err = hipErrorInvalidSymbol;
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+
+bool topk_static_fits(int32_t rows, int32_t V, int32_t k) {
+  const int wpr = (V + TOPK_WAVE_ELEMS - 1) / TOPK_WAVE_ELEMS;
+  return rows >= 0 && rows <= TR_MAX_NODES && V >= 8 && wpr <= TOPK_MAX_WAVES_PER_ROW && k >= 1 && k <= 8;
+}
+
+hipError_t launch_topk_static(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k, int32_t *d_topk,
+                              hipStream_t st) {
+  if (!topk_static_fits(rows, V, k)) return hipErrorInvalidValue;
+  hipError_t e = hipSuccess;
+  void *cand = static_scratch(&e);
+  if (cand == nullptr) return e;
+  // every candidate slot stage 2 reads is written by stage 1 of the same call, so nothing of the
+  // previous call's contents needs clearing
+  return launch_topk(logits, dtype, rows, V, k, d_topk, cand, st);
+}
 
 // ---------------------------------------------------------------------------------------------
 // Matrix update (Section 3.3): M[S[i], :] = topk[i, :] for every node.  A token that occurs more

@@ -136,6 +136,10 @@ hipError_t launch_build_tree(const tr_ctx *c, const int32_t *d_root, int32_t *d_
 hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k,
                        int32_t *d_topk, void *d_cand, hipStream_t s);
 size_t topk_scratch_bytes();
+// the same two-stage kernels on the library's static device scratch (no allocation anywhere)
+bool topk_static_fits(int32_t rows, int32_t V, int32_t k);
+hipError_t launch_topk_static(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k,
+                              int32_t *d_topk, hipStream_t s);
 hipError_t launch_matrix_update(const tr_ctx *c, const int32_t *d_S, const int32_t *d_topk, hipStream_t s);
 // d_tokens: the model's token per node, or NULL for the argmax (first top-k column)
 hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t *d_S,

@@ -81,6 +81,7 @@ _SIGS = {
     "tr_prefill": [C.c_void_p, C.POINTER(Model), C.POINTER(KV), C.c_void_p, C.c_int32, C.c_void_p,
                    C.c_size_t, C.c_void_p],
     "tr_op_topk": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
+    "tr_op_topk_static": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
     "tr_op_matrix_update": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "tr_op_tree_attention": [C.c_void_p, C.POINTER(KV), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                              C.c_void_p, C.c_size_t, C.c_void_p],
@@ -253,6 +254,15 @@ def plan_attention(n_heads: int, n_kv_heads: int, n_nodes: int, len_bound: int):
     plan = (C.c_int32 * 2)()
     _check(lib().tr_plan_attention(n_heads, n_kv_heads, n_nodes, len_bound, plan), "tr_plan_attention")
     return tuple(plan)
+
+
+def op_topk_static(d_logits, d_topk) -> None:
+    """argtopk of every row of d_logits [rows, V] (f32 or bf16) into d_topk [rows, k] int32 through the
+    entry point that allocates nothing (no context; the library's static device scratch)."""
+    import torch
+    dt = TR_BF16 if d_logits.dtype == torch.bfloat16 else TR_F32
+    _check(lib().tr_op_topk_static(_ptr(d_logits), dt, d_logits.shape[0], d_logits.shape[1], d_topk.shape[1],
+                                   _ptr(d_topk), _stream()), "tr_op_topk_static")
 
 
 def op_stream(src, dst=None) -> None:

@@ -159,6 +159,24 @@ def test_attention_plan(lib):
     assert tr.plan_attention(64, 8, 80, 4176)[0] == 2
 
 
+def test_static_topk_validates_before_touching_the_gpu(lib):
+    """The entry point that allocates nothing: argument errors and its size limits are reported
+    from the host, before any HIP call."""
+    buf = np.zeros(64, np.int32)
+    p = buf.ctypes.data
+    f = lib.tr_op_topk_static
+    assert f(None, tr.TR_F32, 4, 64, 8, p, None) == tr.TR_EINVAL
+    assert f(p, tr.TR_F32, 4, 64, 8, None, None) == tr.TR_EINVAL
+    assert f(p, 7, 4, 64, 8, p, None) == tr.TR_EINVAL
+    assert f(p, tr.TR_F32, -1, 64, 8, p, None) == tr.TR_EINVAL
+    assert f(p, tr.TR_F32, 4, 0, 8, p, None) == tr.TR_EINVAL
+    assert f(p, tr.TR_F32, 4, 4, 8, p, None) == tr.TR_EINVAL                      # k > V
+    assert f(p, tr.TR_F32, 4, 64, 9, p, None) == tr.TR_ECAPACITY                  # k beyond the two-stage kernels
+    assert f(p, tr.TR_F32, tr.TR_MAX_NODES + 1, 64, 8, p, None) == tr.TR_ECAPACITY
+    assert f(p, tr.TR_F32, 4, 131073, 8, p, None) == tr.TR_ECAPACITY              # beyond the static scratch
+    assert f(p, tr.TR_F32, 4, 7, 7, p, None) == tr.TR_ECAPACITY                   # V below the kernels' minimum
+
+
 def test_create_rejects_more_candidates_than_tokens(lib):
     st, _ = _create(lib, 4, 8, [-1], [-1], 1)
     assert st == tr.TR_EINVAL
