@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--prompt-len", type=int, default=0,
                     help="0: the prompt length of the shape's workload (7b 512, 13b 2048, 70b 4096)")
     ap.add_argument("--profile-steps", type=int, default=4)
-    ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-steps", type=int, default=4, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--no-ar", action="store_true", help="skip the 1-node autoregressive comparison run")
     ap.add_argument("--no-hot", action="store_true", help="skip the hot-start rerun")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -41,6 +41,10 @@ def parse():
     ap.add_argument("--sweep-nodes", default="",
                     help="comma-separated tree sizes: time the step for each (breadth-first prefixes of the 128-node "
                          "template) instead of the headline run, and print one JSON line with the table")
+    ap.add_argument("--sweep-depth", default="",
+                    help="comma-separated tree depths (layers including the root, 4..8): time the step for 80-node "
+                         "templates of each depth instead of the headline run, cold and with the hot-start matrix "
+                         "the cold run leaves, and print one JSON line with the table")
     ap.add_argument("--sweep-attention", default="",
                     help="comma-separated prefix lengths: time the tree-attention op alone (attention kernel + split "
                          "merge, the shape's heads, 80-node tree, rotating cache layers) at each, instead of the "
@@ -190,6 +194,39 @@ def main():
     total_steps = a.warmup + a.steps + a.profile_steps
     cap = a.prompt_len + total_steps * tmpl.n_layers + tmpl.n_nodes + 64
 
+    if a.sweep_depth:
+        # Step time and accepted length versus tree depth at a fixed 80 nodes (Section 5.1 / Figure 3b).  Step
+        # time barely moves (the forward sees 80 rows whatever their arrangement); what a deeper tree changes is
+        # how many drafts a step can accept, shown here cold and after a hot start (Section 3.1: the same prompt
+        # again with the matrix the first run left behind).
+        if model is None:
+            model = tr.ModelDesc(sh, w)
+        del w
+        rows = []
+        for dd in [int(v) for v in a.sweep_depth.split(",")]:
+            t = synth.depth_template(dd)
+            e = tr.Engine(sh, None, t, k=K, capacity=a.prompt_len + 2 * (a.warmup + a.steps) * t.n_layers + 256,
+                          keep_logits=False, model=model)
+            e.ctx.matrix_load(M0)
+            e.prefill(prompt)
+            timed_steps(e, torch, a.warmup)
+            dts, tk = timed_steps(e, torch, a.steps)
+            e.prefill(prompt)
+            dth, tkh = timed_steps(e, torch, a.steps)
+            rows.append({"n_layers": dd, "n_nodes": t.n_nodes, "layer_sizes": list(t.layer_sizes),
+                         "ms_per_step": dts / a.steps * 1e3, "steps_per_s": a.steps / dts, "mat": tk / a.steps,
+                         "tokens_per_s": tk / dts, "mat_hot_start": tkh / a.steps, "tokens_per_s_hot_start": tkh / dth})
+            say(f"depth {dd}: {rows[-1]['ms_per_step']:.3f} ms/step, MAT {rows[-1]['mat']:.2f} cold, "
+                f"{rows[-1]['mat_hot_start']:.2f} hot")
+            del e
+        print(json.dumps({"metric": "TR step time and accepted length vs tree depth at 80 nodes", "unit": "ms/step",
+                          "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": f"{sh.name}-shape random-init Llama bf16, batch 1, prompt "
+                                                 f"{a.prompt_len}, 80-node templates of 4..8 layers "
+                                                 "(synth.depth_template)"},
+                          "sweep": rows}))
+        return
+
     if a.sweep_nodes:
         # Step time versus tree size (Section 5.1 / Figure 3a asks where verifying more nodes stops being
         # as cheap as one token): same model, prompt and KV length, one engine per tree size.
@@ -244,15 +281,17 @@ def main():
     eng.ctx.profile_enable(False)
     breakdown = {k: {"launches_per_step": v[0] / a.profile_steps, "ms_per_step": v[1] / a.profile_steps}
                  for k, v in prof.items()}
+    # dominant kernel: its own execution time from the start / stop events the library ties to each dispatch
+    # (the figure rocprofv3 --kernel-trace reports for the same launches; profiles/ holds that summary)
     gu_launches, gu_ms = prof["gate_up_swiglu"]
     gu_bytes = 2 * sh.d_ffn * sh.d_model * 2                       # gate + up weights, bf16, read once
-    empty_ms = prof["empty_bracket"][1] / prof["empty_bracket"][0]  # cost of an event pair around nothing
-    gu_avg_s = (gu_ms / gu_launches - empty_ms) * 1e-3
+    gu_avg_s = gu_ms / gu_launches * 1e-3
     achieved = gu_bytes / gu_avg_s / 1e9
     roofline = {"kernel": "gate_up_swiglu (k_gemm_mfma, fused gate/up projection + SwiGLU)", "bound": "hbm",
                 "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
                 "traffic": None, "avg_launch_us": gu_avg_s * 1e6, "algorithmic_bytes_per_launch": gu_bytes,
-                "event_bracket_overhead_us": empty_ms * 1e3}
+                "timing": "per-dispatch start/stop events (hipExtLaunchKernelGGL) over the profiled steps",
+                "rocprof_summary": f"profiles/step_{sh.name}_tree80_kernel_stats.md"}
     # HBM bytes per launch of this kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, if a summary for this
     # workload has been recorded under profiles/ (bench.py cannot run the profiler on itself)
     pmc = os.path.join(ROOT, "profiles", f"gate_up_swiglu_{sh.name}_tree80_pmc.txt")

@@ -346,12 +346,11 @@ tr_status tr_op_stream(const void *d_src, void *d_dst, size_t bytes, void *strea
 /*
  * Per-kernel timing for the time-allocation breakdown (the paper's Figure 6 reports the same
  * split: retrieval / model forward / verification / update).  While enabled, every kernel the
- * step calls launch is bracketed by HIP events on the caller's stream; tr_profile_read
- * synchronises the device, sums elapsed times per kernel class, returns up to max_entries
- * entries ([host]) and resets the counters.  Enabling allocates the event pool (the only
- * allocation after tr_create); events beyond the pool are silently not recorded.  The entry
- * "empty_bracket" times an event pair with no kernel between (once per step): subtract its mean from
- * a launch's elapsed time to get the kernel's own duration.
+ * step calls launch carries a start and a stop event tied to that dispatch, so an entry's time is
+ * the kernels' own execution time (launch latency and the gaps between kernels are not in it);
+ * tr_profile_read synchronises the device, sums the times per kernel class, returns up to
+ * max_entries entries ([host]) and resets the counters.  Enabling allocates the event pool (the
+ * only allocation after tr_create); kernels beyond the pool are launched untimed.
  */
 typedef struct {
   char name[24];

@@ -202,7 +202,6 @@ tr_status tr_matrix_store(tr_ctx *c, int32_t *h_M) {
 
 tr_status tr_build_tree(tr_ctx *c, const int32_t *d_root, int32_t *d_S, void *stream) {
   if (c == nullptr || d_root == nullptr || d_S == nullptr) return TR_EINVAL;
-  ProfScope ps(&c->prof, PC_BUILD, as_stream(stream));
   return launch_build_tree(c, d_root, d_S, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;
 }
 
@@ -243,8 +242,7 @@ tr_status tr_verify_forward(tr_ctx *c, const tr_model *m, tr_kv *kv, const int32
   float *logits = d_logits != nullptr ? d_logits : reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + w.logits);
   hipStream_t st = as_stream(stream);
   if (run_forward(*m, *kv, c->tree, n, d_S, logits, ws, &c->prof, st) != hipSuccess) return TR_EHIP;
-  ProfScope ps(&c->prof, PC_TOPK, st);
-  if (launch_topk(logits, TR_F32, n, m->vocab, c->k, d_topk, c->d_topk_cand, st) != hipSuccess) return TR_EHIP;
+  if (launch_topk(logits, TR_F32, n, m->vocab, c->k, d_topk, c->d_topk_cand, &c->prof, st) != hipSuccess) return TR_EHIP;
   return TR_OK;
 }
 
@@ -255,11 +253,7 @@ static tr_status accept_and_update(tr_ctx *c, tr_kv *kv, const int32_t *d_S, con
   if (s != TR_OK) return s;
   if ((int64_t)kv->len_bound + c->tree.n_nodes > kv->capacity) return TR_ECAPACITY;
   hipStream_t st = as_stream(stream);
-  { ProfScope empty(&c->prof, PC_EMPTY, st); } // an event pair around nothing: the bracket's own cost
-  {
-    ProfScope ps(&c->prof, PC_ACCEPT, st);
-    if (launch_accept_update(c, kv, d_S, d_topk, d_tokens, d_out, st) != hipSuccess) return TR_EHIP;
-  }
+  if (launch_accept_update(c, kv, d_S, d_topk, d_tokens, d_out, st) != hipSuccess) return TR_EHIP;
   if (h_out != nullptr) {
     if (hipMemcpyAsync(h_out, d_out, sizeof(tr_step_out), hipMemcpyDeviceToHost, st) != hipSuccess) return TR_EHIP;
     if (hipStreamSynchronize(st) != hipSuccess) return TR_EHIP;
@@ -315,7 +309,9 @@ tr_status tr_prefill(tr_ctx *c, const tr_model *m, tr_kv *kv, const int32_t *d_t
 tr_status tr_op_topk(tr_ctx *c, const void *d_logits, int32_t dtype, int32_t n_rows, int32_t *d_topk, void *stream) {
   if (c == nullptr || d_logits == nullptr || d_topk == nullptr || n_rows < 0) return TR_EINVAL;
   if (dtype != TR_F32 && dtype != TR_BF16) return TR_EINVAL;
-  return launch_topk(d_logits, dtype, n_rows, c->V, c->k, d_topk, c->d_topk_cand, as_stream(stream)) == hipSuccess ? TR_OK : TR_EHIP;
+  return launch_topk(d_logits, dtype, n_rows, c->V, c->k, d_topk, c->d_topk_cand, nullptr, as_stream(stream)) == hipSuccess
+             ? TR_OK
+             : TR_EHIP;
 }
 
 tr_status tr_op_topk_static(const void *d_logits, int32_t dtype, int32_t n_rows, int32_t V, int32_t k,
@@ -402,9 +398,10 @@ tr_status tr_profile_enable(tr_ctx *c, int32_t enable) {
 }
 
 tr_status tr_profile_read(tr_ctx *c, tr_profile_entry *h, int32_t max_entries, int32_t *n_entries) {
-  static const char *const names[PC_COUNT] = {"build_tree", "embed_rope_table", "rmsnorm", "qkv_proj", "rope_kv_write",
-                                              "tree_attention", "o_proj", "gate_up_swiglu", "down_proj", "lm_head",
-                                              "topk", "accept_update_compact", "empty_bracket"};
+  static const char *const names[PC_COUNT] = {"build_tree", "embed_rope_table", "residual_norm", "qkv_proj",
+                                              "rope_kv_write", "tree_attention", "attention_merge", "o_proj",
+                                              "gate_up_swiglu", "down_proj", "lm_head", "topk", "topk_merge",
+                                              "accept_update", "compact_kv", "sample_tokens"};
   if (c == nullptr || h == nullptr || n_entries == nullptr || max_entries < 0) return TR_EINVAL;
   Profiler &p = c->prof;
   if (hipDeviceSynchronize() != hipSuccess) return TR_EHIP;

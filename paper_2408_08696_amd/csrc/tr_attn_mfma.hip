@@ -305,45 +305,45 @@ int attn_choose_splits(int32_t head_groups, int32_t len_bound) {
 template <int NT, int HPW>
 static hipError_t launch_attn_k(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                                 int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t nsplit, float *part_ml,
-                                float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st) {
-  hipLaunchKernelGGL((k_attn_mfma<NT, HPW>), dim3(Hkv, H / Hkv / HPW, nsplit), dim3(NT * HPW * 64), 0, st, q, Kl, Vl, H, Hkv, cap,
-                     n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles);
-  return hipGetLastError();
+                                float *part_acc, bf16_t *out, int32_t out_row_tiles, KernelTimer tm, hipStream_t st) {
+  return launch(k_attn_mfma<NT, HPW>, dim3(Hkv, H / Hkv / HPW, nsplit), dim3(NT * HPW * 64), 0, st, tm, q, Kl, Vl, H, Hkv,
+                cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles);
 }
 
 template <int NT>
 static hipError_t launch_attn_nt(int hpw, const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv,
                                  int32_t cap, int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t nsplit,
-                                 float *part_ml, float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st) {
+                                 float *part_ml, float *part_acc, bf16_t *out, int32_t out_row_tiles, KernelTimer tm,
+                                 hipStream_t st) {
   if constexpr (NT <= 6) {
     if (hpw == 2)
-      return launch_attn_k<NT, 2>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st);
+      return launch_attn_k<NT, 2>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st);
   }
   if (hpw != 1) return hipErrorInvalidValue;
-  return launch_attn_k<NT, 1>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st);
+  return launch_attn_k<NT, 1>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st);
 }
 
 hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                             int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t len_bound, float *part_ml,
-                            float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st) {
+                            float *part_acc, bf16_t *out, int32_t out_row_tiles, Profiler *prof, hipStream_t st) {
   if (Hkv < 1 || H % Hkv != 0) return hipErrorInvalidValue;
+  const KernelTimer tm = prof_next(prof, PC_ATTN);
   const int hpw = attn_heads_per_wg(H, Hkv, n);
   const int nsplit = attn_choose_splits(H / hpw, len_bound);
   hipError_t e = hipErrorInvalidValue;
   switch ((n + 15) / 16) {
-  case 1: e = launch_attn_nt<1>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 2: e = launch_attn_nt<2>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 3: e = launch_attn_nt<3>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 4: e = launch_attn_nt<4>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 5: e = launch_attn_nt<5>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 6: e = launch_attn_nt<6>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 7: e = launch_attn_nt<7>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
-  case 8: e = launch_attn_nt<8>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, st); break;
+  case 1: e = launch_attn_nt<1>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
+  case 2: e = launch_attn_nt<2>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
+  case 3: e = launch_attn_nt<3>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
+  case 4: e = launch_attn_nt<4>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
+  case 5: e = launch_attn_nt<5>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
+  case 6: e = launch_attn_nt<6>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
+  case 7: e = launch_attn_nt<7>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
+  case 8: e = launch_attn_nt<8>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
   }
   if (e != hipSuccess || nsplit == 1) return e;
-  hipLaunchKernelGGL(k_attn_merge, dim3((n + 7) / 8, H), dim3(256), 0, st, part_ml, part_acc, H, n, nsplit, out,
-                     out_row_tiles);
-  return hipGetLastError();
+  return launch(k_attn_merge, dim3((n + 7) / 8, H), dim3(256), 0, st, prof_next(prof, PC_ATTN_MERGE), part_ml, part_acc, H,
+                n, nsplit, out, out_row_tiles);
 }
 
 } // namespace tr

@@ -131,10 +131,9 @@ __global__ __launch_bounds__(256) void k_linear_generic(const T *__restrict__ a,
 
 template <typename T>
 static hipError_t linear_generic(const void *a, const void *w, int32_t n, int32_t K, int32_t O, float *y, int32_t ldy,
-                                 int32_t mode, hipStream_t st) {
-  hipLaunchKernelGGL(k_linear_generic<T>, dim3((O + 3) / 4, (n + 15) / 16), dim3(256), 0, st, (const T *)a,
-                     (const T *)w, n, K, O, y, ldy, mode);
-  return hipGetLastError();
+                                 int32_t mode, hipStream_t st, KernelTimer tm = KernelTimer{}) {
+  return launch(k_linear_generic<T>, dim3((O + 3) / 4, (n + 15) / 16), dim3(256), 0, st, tm, (const T *)a, (const T *)w, n,
+                K, O, y, ldy, mode);
 }
 
 // h[n,f] = T(silu(g) * u) with gu = [gate | up], each F wide
@@ -296,18 +295,17 @@ __global__ __launch_bounds__(256) void k_attn_generic(const T *__restrict__ q, c
 template <typename T>
 static hipError_t attention_dispatch(const tr_kv &kv, int32_t layer, int32_t H, const TreeDev &tree, int32_t n,
                                      const T *q, T *out, int32_t out_row_tiles, float *part_ml, float *part_acc,
-                                     hipStream_t st) {
+                                     Profiler *prof, hipStream_t st) {
   const size_t lsz = (size_t)kv.n_kv_heads * kv.capacity * kv.head_dim;
   const T *Kl = (const T *)kv.k + (size_t)layer * lsz;
   const T *Vl = (const T *)kv.v + (size_t)layer * lsz;
   if (kv.layout == TR_KV_TILED) {
     return launch_attn_mfma((const bf16_t *)q, (const bf16_t *)Kl, (const bf16_t *)Vl, H, kv.n_kv_heads, kv.capacity,
                             n, tree.anc, kv.d_len, kv.len_bound + n, part_ml, part_acc, (bf16_t *)out, out_row_tiles,
-                            st);
+                            prof, st);
   }
-  hipLaunchKernelGGL(k_attn_generic<T>, dim3(n, H), dim3(256), 0, st, q, Kl, Vl, H, kv.n_kv_heads, kv.head_dim,
-                     kv.capacity, n, tree.anc, kv.d_len, out, out_row_tiles);
-  return hipGetLastError();
+  return launch(k_attn_generic<T>, dim3(n, H), dim3(256), 0, st, prof_next(prof, PC_ATTN), q, Kl, Vl, H, kv.n_kv_heads,
+                kv.head_dim, kv.capacity, n, tree.anc, kv.d_len, out, out_row_tiles);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -330,65 +328,32 @@ static hipError_t forward_generic(const tr_model &m, const tr_kv &kv, const Tree
   float *rope = (float *)(ws + w.rope);
   const size_t lsz = (size_t)Hkv * kv.capacity * hd;
 
-  {
-    ProfScope ps(prof, PC_EMBED, st);
-    hipLaunchKernelGGL(k_embed_rope<T>, dim3(n), dim3(256), 0, st, (const T *)m.embed, m.vocab, d, tok, tree.depth,
-                       kv.d_len, hd, m.rope_theta, x, rope);
-    TR_TRY(hipGetLastError());
-  }
+  TR_TRY(launch(k_embed_rope<T>, dim3(n), dim3(256), 0, st, prof_next(prof, PC_EMBED), (const T *)m.embed, m.vocab, d, tok,
+                tree.depth, kv.d_len, hd, m.rope_theta, x, rope));
   for (int l = 0; l < m.n_layers; ++l) {
     const tr_layer &lw = m.layers[l];
-    {
-      ProfScope ps(prof, PC_NORM, st);
-      hipLaunchKernelGGL(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, x, (const T *)lw.attn_norm, d, m.rms_eps, xn);
-      TR_TRY(hipGetLastError());
-    }
-    {
-      ProfScope ps(prof, PC_QKV, st);
-      TR_TRY(linear_generic<T>(xn, lw.wq, n, d, hq, qkv, wq, 0, st));
-      TR_TRY(linear_generic<T>(xn, lw.wk, n, d, hk, qkv + hq, wq, 0, st));
-      TR_TRY(linear_generic<T>(xn, lw.wv, n, d, hk, qkv + hq + hk, wq, 0, st));
-    }
-    {
-      ProfScope ps(prof, PC_ROPE, st);
-      hipLaunchKernelGGL(k_rope_kv<T>, dim3(n, (H + 2 * Hkv + ROPE_HPB - 1) / ROPE_HPB), dim3(256), 0, st, qkv, 1, (size_t)0, rope, H, Hkv, hd,
-                         kv.capacity, kv.d_len, q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, kv.layout);
-      TR_TRY(hipGetLastError());
-    }
-    {
-      ProfScope ps(prof, PC_ATTN, st);
-      TR_TRY(attention_dispatch<T>(kv, l, H, tree, n, q, attn, 0, (float *)(ws + w.part_ml),
-                                   (float *)(ws + w.part_acc), st));
-    }
-    {
-      ProfScope ps(prof, PC_OPROJ, st);
-      TR_TRY(linear_generic<T>(attn, lw.wo, n, hq, d, x, d, 1, st));
-    }
-    {
-      ProfScope ps(prof, PC_NORM, st);
-      hipLaunchKernelGGL(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, x, (const T *)lw.ffn_norm, d, m.rms_eps, xn);
-      TR_TRY(hipGetLastError());
-    }
-    {
-      ProfScope ps(prof, PC_GATEUP, st);
-      TR_TRY(linear_generic<T>(xn, lw.w_gate, n, d, F, gu, 2 * F, 0, st));
-      TR_TRY(linear_generic<T>(xn, lw.w_up, n, d, F, gu + F, 2 * F, 0, st));
-      hipLaunchKernelGGL(k_swiglu<T>, dim3((F + 255) / 256, n), dim3(256), 0, st, gu, F, hbuf);
-      TR_TRY(hipGetLastError());
-    }
-    {
-      ProfScope ps(prof, PC_DOWN, st);
-      TR_TRY(linear_generic<T>(hbuf, lw.w_down, n, F, d, x, d, 1, st));
-    }
+    TR_TRY(launch(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, prof_next(prof, PC_NORM), x, (const T *)lw.attn_norm, d,
+                  m.rms_eps, xn));
+    TR_TRY(linear_generic<T>(xn, lw.wq, n, d, hq, qkv, wq, 0, st, prof_next(prof, PC_QKV)));
+    TR_TRY(linear_generic<T>(xn, lw.wk, n, d, hk, qkv + hq, wq, 0, st, prof_next(prof, PC_QKV)));
+    TR_TRY(linear_generic<T>(xn, lw.wv, n, d, hk, qkv + hq + hk, wq, 0, st, prof_next(prof, PC_QKV)));
+    TR_TRY(launch(k_rope_kv<T>, dim3(n, (H + 2 * Hkv + ROPE_HPB - 1) / ROPE_HPB), dim3(256), 0, st,
+                  prof_next(prof, PC_ROPE), qkv, 1, (size_t)0, rope, H, Hkv, hd, kv.capacity, kv.d_len, q,
+                  (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, kv.layout));
+    TR_TRY(attention_dispatch<T>(kv, l, H, tree, n, q, attn, 0, (float *)(ws + w.part_ml), (float *)(ws + w.part_acc),
+                                 prof, st));
+    TR_TRY(linear_generic<T>(attn, lw.wo, n, hq, d, x, d, 1, st, prof_next(prof, PC_OPROJ)));
+    TR_TRY(launch(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, prof_next(prof, PC_NORM), x, (const T *)lw.ffn_norm, d,
+                  m.rms_eps, xn));
+    TR_TRY(linear_generic<T>(xn, lw.w_gate, n, d, F, gu, 2 * F, 0, st, prof_next(prof, PC_GATEUP)));
+    TR_TRY(linear_generic<T>(xn, lw.w_up, n, d, F, gu + F, 2 * F, 0, st, prof_next(prof, PC_GATEUP)));
+    TR_TRY(launch(k_swiglu<T>, dim3((F + 255) / 256, n), dim3(256), 0, st, prof_next(prof, PC_GATEUP), gu, F, hbuf));
+    TR_TRY(linear_generic<T>(hbuf, lw.w_down, n, F, d, x, d, 1, st, prof_next(prof, PC_DOWN)));
   }
   if (logits_out != nullptr) {
-    {
-      ProfScope ps(prof, PC_NORM, st);
-      hipLaunchKernelGGL(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, x, (const T *)m.final_norm, d, m.rms_eps, xn);
-      TR_TRY(hipGetLastError());
-    }
-    ProfScope ps(prof, PC_LMHEAD, st);
-    TR_TRY(linear_generic<T>(xn, m.lm_head, n, d, m.vocab, logits_out, m.vocab, 0, st));
+    TR_TRY(launch(k_rmsnorm<T>, dim3(n), dim3(256), 0, st, prof_next(prof, PC_NORM), x, (const T *)m.final_norm, d,
+                  m.rms_eps, xn));
+    TR_TRY(linear_generic<T>(xn, m.lm_head, n, d, m.vocab, logits_out, m.vocab, 0, st, prof_next(prof, PC_LMHEAD)));
   }
   return hipSuccess;
 }
@@ -480,7 +445,7 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
   typedef bf16_t T;
   const Workspace w = plan_workspace(m);
   const int d = m.d_model, H = m.n_heads, Hkv = m.n_kv_heads, hd = m.head_dim, F = m.d_ffn;
-  const int hq = H * hd, hk = Hkv * hd, wq = hq + 2 * hk;
+  const int hq = H * hd, hk = Hkv * hd;
   const int NT = (n + 15) / 16;
   float *x = (float *)(ws + w.x);
   T *xn = (T *)(ws + w.xn);
@@ -491,27 +456,20 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
   float *ypart = (float *)(ws + w.ypart);
   const size_t ystride = (size_t)NP * d;
   const size_t lsz = (size_t)Hkv * kv.capacity * hd;
-  const size_t qstride = (size_t)NP * wq;
   float *ssq = (float *)(ws + w.ssq);
   const int nch = (d + NORM_CHUNK - 1) / NORM_CHUNK;
 
-  {
-    ProfScope ps(prof, PC_EMBED, st);
-    hipLaunchKernelGGL(k_embed_rope<T>, dim3(n), dim3(256), 0, st, (const T *)m.embed, m.vocab, d, tok, tree.depth,
-                       kv.d_len, hd, m.rope_theta, x, rope);
-    TR_TRY(hipGetLastError());
-  }
+  TR_TRY(launch(k_embed_rope<T>, dim3(n), dim3(256), 0, st, prof_next(prof, PC_EMBED), (const T *)m.embed, m.vocab, d, tok,
+                tree.depth, kv.d_len, hd, m.rope_theta, x, rope));
   int pending = 0; // partial sums waiting in ypart
+  auto add_norm = [&](const void *gain) {
+    return launch(k_add_frag, dim3(NT * 16, nch), dim3(128), 0, st, prof_next(prof, PC_NORM), x, ypart, pending, ystride,
+                  (const T *)gain, n, d, NT, xn, ssq, nch);
+  };
   for (int l = 0; l < m.n_layers; ++l) {
     const tr_layer &lw = m.layers[l];
+    TR_TRY(add_norm(lw.attn_norm));
     {
-      ProfScope ps(prof, PC_NORM, st);
-      hipLaunchKernelGGL(k_add_frag, dim3(NT * 16, nch), dim3(128), 0, st, x, ypart, pending, ystride,
-                         (const T *)lw.attn_norm, n, d, NT, xn, ssq, nch);
-      TR_TRY(hipGetLastError());
-    }
-    {
-      ProfScope ps(prof, PC_QKV, st);
       GemmArgs g{};
       g.a_frag = xn; g.n = n; g.K = d;
       g.seg[0] = GemmSeg{(const T *)lw.wq, hq / 16};
@@ -524,65 +482,48 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
       g.rope = GemmRope{q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, rope, kv.d_len,
                         H, Hkv, hd, kv.capacity, kv.layout};
       gemm_plan(g, 1);
-      TR_TRY(launch_gemm_mfma(g, st));
+      TR_TRY(launch_gemm_mfma(g, st, prof_next(prof, PC_QKV)));
     }
+    TR_TRY(attention_dispatch<T>(kv, l, H, tree, n, q, attn, NT, (float *)(ws + w.part_ml), (float *)(ws + w.part_acc),
+                                 prof, st));
     {
-      ProfScope ps(prof, PC_ATTN, st);
-      TR_TRY(attention_dispatch<T>(kv, l, H, tree, n, q, attn, NT, (float *)(ws + w.part_ml),
-                                   (float *)(ws + w.part_acc), st));
-    }
-    {
-      ProfScope ps(prof, PC_OPROJ, st);
       GemmArgs g{};
       g.a_frag = attn; g.n = n; g.K = hq;
       g.seg[0] = GemmSeg{(const T *)lw.wo, d / 16};
       g.n_seg = 1; g.y = ypart; g.ldy = d; g.split_stride = ystride; g.mode = GEMM_STORE;
       gemm_plan(g, GEMM_MAX_SPLITS);
       pending = g.splits;
-      TR_TRY(launch_gemm_mfma(g, st));
+      TR_TRY(launch_gemm_mfma(g, st, prof_next(prof, PC_OPROJ)));
     }
+    TR_TRY(add_norm(lw.ffn_norm));
     {
-      ProfScope ps(prof, PC_NORM, st);
-      hipLaunchKernelGGL(k_add_frag, dim3(NT * 16, nch), dim3(128), 0, st, x, ypart, pending, ystride,
-                         (const T *)lw.ffn_norm, n, d, NT, xn, ssq, nch);
-      TR_TRY(hipGetLastError());
-    }
-    {
-      ProfScope ps(prof, PC_GATEUP, st);
       GemmArgs g{};
       g.a_frag = xn; g.n = n; g.K = d;
       g.seg[0] = GemmSeg{(const T *)lw.w_gate, F / 16};
       g.n_seg = 1; g.w2 = (const T *)lw.w_up; g.h_frag = hbuf; g.mode = GEMM_SWIGLU;
       g.row_ssq = ssq; g.n_ssq = nch; g.norm_dim = d; g.eps = m.rms_eps;
       gemm_plan(g, 1);
-      TR_TRY(launch_gemm_mfma(g, st));
+      TR_TRY(launch_gemm_mfma(g, st, prof_next(prof, PC_GATEUP)));
     }
     {
-      ProfScope ps(prof, PC_DOWN, st);
       GemmArgs g{};
       g.a_frag = hbuf; g.n = n; g.K = F;
       g.seg[0] = GemmSeg{(const T *)lw.w_down, d / 16};
       g.n_seg = 1; g.y = ypart; g.ldy = d; g.split_stride = ystride; g.mode = GEMM_STORE;
       gemm_plan(g, GEMM_MAX_SPLITS);
       pending = g.splits;
-      TR_TRY(launch_gemm_mfma(g, st));
+      TR_TRY(launch_gemm_mfma(g, st, prof_next(prof, PC_DOWN)));
     }
   }
   if (logits_out != nullptr) {
-    {
-      ProfScope ps(prof, PC_NORM, st);
-      hipLaunchKernelGGL(k_add_frag, dim3(NT * 16, nch), dim3(128), 0, st, x, ypart, pending, ystride,
-                         (const T *)m.final_norm, n, d, NT, xn, ssq, nch);
-      TR_TRY(hipGetLastError());
-    }
-    ProfScope ps(prof, PC_LMHEAD, st);
+    TR_TRY(add_norm(m.final_norm));
     GemmArgs g{};
     g.a_frag = xn; g.n = n; g.K = d;
     g.seg[0] = GemmSeg{(const T *)m.lm_head, m.vocab / 16};
     g.n_seg = 1; g.y = logits_out; g.ldy = m.vocab; g.split_stride = 0; g.mode = GEMM_STORE;
     g.row_ssq = ssq; g.n_ssq = nch; g.norm_dim = d; g.eps = m.rms_eps;
     gemm_plan(g, 1);
-    TR_TRY(launch_gemm_mfma(g, st));
+    TR_TRY(launch_gemm_mfma(g, st, prof_next(prof, PC_LMHEAD)));
   }
   return hipSuccess;
 }
@@ -604,9 +545,9 @@ hipError_t run_tree_attention(const tr_kv &kv, int32_t layer, int32_t H, const T
   float *acc = ws ? (float *)((unsigned char *)ws + align256((size_t)ATTN_MAX_SPLITS * NP * H * 2 * 4)) : nullptr;
   if (kv.dtype == TR_BF16)
     return attention_dispatch<bf16_t>(kv, layer, H, tree, tree.n_nodes, (const bf16_t *)d_q, (bf16_t *)d_out, 0, ml,
-                                      acc, st);
+                                      acc, nullptr, st);
   return attention_dispatch<float>(kv, layer, H, tree, tree.n_nodes, (const float *)d_q, (float *)d_out, 0, nullptr,
-                                   nullptr, st);
+                                   nullptr, nullptr, st);
 }
 
 size_t linear_workspace_bytes(int32_t n, int32_t in_f, int32_t out_f, int32_t splits) {
@@ -620,8 +561,7 @@ hipError_t run_linear(const void *x, const void *w, int32_t dtype, int32_t layou
     const int NT = (n + 15) / 16;
     bf16_t *frag = (bf16_t *)ws;
     float *part = (float *)((unsigned char *)ws + align256((size_t)NT * 16 * in_f * 2));
-    hipLaunchKernelGGL(k_rows_to_frag, dim3(NT * 16), dim3(256), 0, st, (const bf16_t *)x, n, in_f, NT, frag);
-    TR_TRY(hipGetLastError());
+    TR_TRY(launch(k_rows_to_frag, dim3(NT * 16), dim3(256), 0, st, KernelTimer{}, (const bf16_t *)x, n, in_f, NT, frag));
     GemmArgs g{};
     g.a_frag = frag; g.n = n; g.K = in_f;
     g.seg[0] = GemmSeg{(const bf16_t *)w, out_f / 16};
@@ -632,9 +572,8 @@ hipError_t run_linear(const void *x, const void *w, int32_t dtype, int32_t layou
     TR_TRY(launch_gemm_mfma(g, st));
     if (splits > 1) {
       const size_t count = (size_t)n * out_f;
-      hipLaunchKernelGGL(k_sum_parts, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, part, splits,
-                         (size_t)n * out_f, count, y);
-      TR_TRY(hipGetLastError());
+      TR_TRY(launch(k_sum_parts, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, KernelTimer{}, part, splits,
+                    (size_t)n * out_f, count, y));
     }
     return hipSuccess;
   }

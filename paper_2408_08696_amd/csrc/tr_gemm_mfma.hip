@@ -74,9 +74,8 @@ __global__ __launch_bounds__(256) void k_pack_weight(const bf16_t *__restrict__ 
 
 hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t K, int32_t rope_hd, hipStream_t st) {
   const size_t total = (size_t)(O / 16) * (K / 32) * 64;
-  hipLaunchKernelGGL(k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, src, O, K, rope_hd,
-                     reinterpret_cast<uint4 *>(dst));
-  return hipGetLastError();
+  return launch(k_pack_weight, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, KernelTimer{}, src, O, K, rope_hd,
+                reinterpret_cast<uint4 *>(dst));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -360,7 +359,7 @@ void gemm_choose(int32_t n, int32_t K, int32_t total_tiles, bool swiglu, int32_t
 }
 
 template <int NT, int P, int MODE, int GW, bool SCALED>
-static hipError_t launch_ks(const GemmArgs &g, hipStream_t st) {
+static hipError_t launch_ks(const GemmArgs &g, hipStream_t st, KernelTimer tm) {
   constexpr int NW = MODE == GEMM_SWIGLU ? 2 * P : P;
   const size_t smem = gemm_tail_red_bytes(P, NT, MODE, GW, SCALED) + gemm_scale_lds_bytes(NT, SCALED);
   if (smem > 65536) {
@@ -370,19 +369,18 @@ static hipError_t launch_ks(const GemmArgs &g, hipStream_t st) {
     }();
     if (!once) return hipErrorInvalidValue;
   }
-  hipLaunchKernelGGL((k_gemm_mfma<NT, NW, MODE, GW, SCALED>), dim3(g.groups, g.splits), dim3(GW * 64), smem, st, g);
-  return hipGetLastError();
+  return launch(k_gemm_mfma<NT, NW, MODE, GW, SCALED>, dim3(g.groups, g.splits), dim3(GW * 64), smem, st, tm, g);
 }
 // the epilogue's RMS scale is a compile-time property: without it the tail needs no scale hand-out and
 // the whole of LDS can hold partial tiles
 template <int NT, int P, int MODE, int GW = GEMM_WAVES>
-static hipError_t launch_k(const GemmArgs &g, hipStream_t st) {
-  if (g.row_ssq != nullptr) return launch_ks<NT, P, MODE, GW, true>(g, st);
-  return launch_ks<NT, P, MODE, GW, false>(g, st);
+static hipError_t launch_k(const GemmArgs &g, hipStream_t st, KernelTimer tm) {
+  if (g.row_ssq != nullptr) return launch_ks<NT, P, MODE, GW, true>(g, st, tm);
+  return launch_ks<NT, P, MODE, GW, false>(g, st, tm);
 }
 
 template <int NT>
-static hipError_t launch_nt(const GemmArgs &g, hipStream_t st) {
+static hipError_t launch_nt(const GemmArgs &g, hipStream_t st, KernelTimer tm) {
   const int p = g.tiles_per_wg;
   const bool swiglu = g.mode == GEMM_SWIGLU;
   if (!variant_ok(NT, p, swiglu) || g.groups < 1 || g.groups > g.total_tiles ||
@@ -390,51 +388,51 @@ static hipError_t launch_nt(const GemmArgs &g, hipStream_t st) {
     return hipErrorInvalidValue;
   if (swiglu) {
     if constexpr (NT == 4 || NT == 5) {
-      if (p == 4) return launch_k<NT, 4, GEMM_SWIGLU, 4>(g, st);
+      if (p == 4) return launch_k<NT, 4, GEMM_SWIGLU, 4>(g, st, tm);
     }
     if constexpr (NT <= 5) {
-      if (p == 3) return launch_k<NT, 3, GEMM_SWIGLU>(g, st);
+      if (p == 3) return launch_k<NT, 3, GEMM_SWIGLU>(g, st, tm);
     } else {
-      if (p == 3) return launch_k<NT, 3, GEMM_SWIGLU, 4>(g, st);
+      if (p == 3) return launch_k<NT, 3, GEMM_SWIGLU, 4>(g, st, tm);
     }
-    if (p == 2) return launch_k<NT, 2, GEMM_SWIGLU>(g, st);
-    if (p == 1) return launch_k<NT, 1, GEMM_SWIGLU>(g, st);
+    if (p == 2) return launch_k<NT, 2, GEMM_SWIGLU>(g, st, tm);
+    if (p == 1) return launch_k<NT, 1, GEMM_SWIGLU>(g, st, tm);
     return hipErrorInvalidValue;
   }
   if constexpr (NT == 4 || NT == 5) {
-    if (p == 8) return launch_k<NT, 8, GEMM_STORE, 4>(g, st);
+    if (p == 8) return launch_k<NT, 8, GEMM_STORE, 4>(g, st, tm);
   }
   if constexpr (NT <= 5) {
-    if (p == 6) return launch_k<NT, 6, GEMM_STORE>(g, st);
+    if (p == 6) return launch_k<NT, 6, GEMM_STORE>(g, st, tm);
   } else {
-    if (p == 6) return launch_k<NT, 6, GEMM_STORE, 4>(g, st);
+    if (p == 6) return launch_k<NT, 6, GEMM_STORE, 4>(g, st, tm);
   }
   if constexpr (NT <= 5) {
-    if (p == 5) return launch_k<NT, 5, GEMM_STORE>(g, st);
+    if (p == 5) return launch_k<NT, 5, GEMM_STORE>(g, st, tm);
   }
   switch (p) {
-  case 1: return launch_k<NT, 1, GEMM_STORE>(g, st);
-  case 2: return launch_k<NT, 2, GEMM_STORE>(g, st);
-  case 3: return launch_k<NT, 3, GEMM_STORE>(g, st);
-  case 4: return launch_k<NT, 4, GEMM_STORE>(g, st);
+  case 1: return launch_k<NT, 1, GEMM_STORE>(g, st, tm);
+  case 2: return launch_k<NT, 2, GEMM_STORE>(g, st, tm);
+  case 3: return launch_k<NT, 3, GEMM_STORE>(g, st, tm);
+  case 4: return launch_k<NT, 4, GEMM_STORE>(g, st, tm);
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_gemm_mfma(const GemmArgs &args, hipStream_t st) {
+hipError_t launch_gemm_mfma(const GemmArgs &args, hipStream_t st, KernelTimer tm) {
   if (args.groups < 1 || args.total_tiles < 1) return hipErrorInvalidValue;
   GemmArgs g = args;
   g.part_q = g.total_tiles / g.groups;
   g.part_rem = g.total_tiles % g.groups;
   switch ((g.n + 15) / 16) {
-  case 1: return launch_nt<1>(g, st);
-  case 2: return launch_nt<2>(g, st);
-  case 3: return launch_nt<3>(g, st);
-  case 4: return launch_nt<4>(g, st);
-  case 5: return launch_nt<5>(g, st);
-  case 6: return launch_nt<6>(g, st);
-  case 7: return launch_nt<7>(g, st);
-  case 8: return launch_nt<8>(g, st);
+  case 1: return launch_nt<1>(g, st, tm);
+  case 2: return launch_nt<2>(g, st, tm);
+  case 3: return launch_nt<3>(g, st, tm);
+  case 4: return launch_nt<4>(g, st, tm);
+  case 5: return launch_nt<5>(g, st, tm);
+  case 6: return launch_nt<6>(g, st, tm);
+  case 7: return launch_nt<7>(g, st, tm);
+  case 8: return launch_nt<8>(g, st, tm);
   }
   return hipErrorInvalidValue;
 }

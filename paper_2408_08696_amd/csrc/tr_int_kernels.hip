@@ -36,10 +36,9 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_build_tree(const int32_t *__re
   if (live) S[i] = s[i];
 }
 
-hipError_t launch_build_tree(const tr_ctx *c, const int32_t *d_root, int32_t *d_S, hipStream_t st) {
-  hipLaunchKernelGGL(k_build_tree, dim3(1), dim3(TR_MAX_NODES), 0, st, c->d_M, c->V, c->k, c->tree,
-                     d_root, d_S);
-  return hipGetLastError();
+hipError_t launch_build_tree(tr_ctx *c, const int32_t *d_root, int32_t *d_S, hipStream_t st) {
+  return launch(k_build_tree, dim3(1), dim3(TR_MAX_NODES), 0, st, c->prof.next(PC_BUILD), c->d_M, c->V, c->k, c->tree,
+                d_root, d_S);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -190,7 +189,7 @@ __global__ __launch_bounds__(64) void k_topk_stage2(const uint64_t *__restrict__
 }
 
 hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k, int32_t *d_topk,
-                       void *d_cand, hipStream_t st) {
+                       void *d_cand, Profiler *prof, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
   const size_t esz = dtype_size(dtype);
   const int wpr = (V + TOPK_WAVE_ELEMS - 1) / TOPK_WAVE_ELEMS;
@@ -199,22 +198,25 @@ hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t 
     for (int r0 = 0; r0 < rows; r0 += TR_MAX_NODES) { // the candidate scratch holds TR_MAX_NODES rows
       const int nr = rows - r0 < TR_MAX_NODES ? rows - r0 : TR_MAX_NODES;
       const char *src = (const char *)logits + (size_t)r0 * V * esz;
+      hipError_t e;
       if (dtype == TR_BF16)
-        hipLaunchKernelGGL(k_topk_stage1<bf16_t>, dim3(wg_per_row, nr), dim3(TOPK1_THREADS), 0, st, (const bf16_t *)src,
-                           V, k, wpr, (uint64_t *)d_cand);
+        e = launch(k_topk_stage1<bf16_t>, dim3(wg_per_row, nr), dim3(TOPK1_THREADS), 0, st, prof_next(prof, PC_TOPK),
+                   (const bf16_t *)src, V, k, wpr, (uint64_t *)d_cand);
       else
-        hipLaunchKernelGGL(k_topk_stage1<float>, dim3(wg_per_row, nr), dim3(TOPK1_THREADS), 0, st, (const float *)src, V,
-                           k, wpr, (uint64_t *)d_cand);
-      hipLaunchKernelGGL(k_topk_stage2, dim3(nr), dim3(64), 0, st, (const uint64_t *)d_cand, k, wpr,
-                         d_topk + (size_t)r0 * k);
+        e = launch(k_topk_stage1<float>, dim3(wg_per_row, nr), dim3(TOPK1_THREADS), 0, st, prof_next(prof, PC_TOPK),
+                   (const float *)src, V, k, wpr, (uint64_t *)d_cand);
+      if (e != hipSuccess) return e;
+      e = launch(k_topk_stage2, dim3(nr), dim3(64), 0, st, prof_next(prof, PC_TOPK_MERGE), (const uint64_t *)d_cand, k,
+                 wpr, d_topk + (size_t)r0 * k);
+      if (e != hipSuccess) return e;
     }
-    return hipGetLastError();
+    return hipSuccess;
   }
   if (dtype == TR_BF16)
-    hipLaunchKernelGGL(k_topk<bf16_t>, dim3(rows), dim3(TOPK_THREADS), 0, st, (const bf16_t *)logits, V, k, d_topk);
-  else
-    hipLaunchKernelGGL(k_topk<float>, dim3(rows), dim3(TOPK_THREADS), 0, st, (const float *)logits, V, k, d_topk);
-  return hipGetLastError();
+    return launch(k_topk<bf16_t>, dim3(rows), dim3(TOPK_THREADS), 0, st, prof_next(prof, PC_TOPK), (const bf16_t *)logits,
+                  V, k, d_topk);
+  return launch(k_topk<float>, dim3(rows), dim3(TOPK_THREADS), 0, st, prof_next(prof, PC_TOPK), (const float *)logits, V,
+                k, d_topk);
 }
 
 size_t topk_scratch_bytes() { return (size_t)TR_MAX_NODES * TOPK_MAX_WAVES_PER_ROW * 8 * sizeof(uint64_t); }
@@ -267,7 +269,7 @@ hipError_t launch_topk_static(const void *logits, int32_t dtype, int32_t rows, i
   if (cand == nullptr) return e;
   // every candidate slot stage 2 reads is written by stage 1 of the same call, so nothing of the
   // previous call's contents needs clearing
-  return launch_topk(logits, dtype, rows, V, k, d_topk, cand, st);
+  return launch_topk(logits, dtype, rows, V, k, d_topk, cand, nullptr, st);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -308,9 +310,8 @@ __global__ __launch_bounds__(TR_MAX_NODES) void k_matrix_update(int32_t *__restr
 }
 
 hipError_t launch_matrix_update(const tr_ctx *c, const int32_t *d_S, const int32_t *d_topk, hipStream_t st) {
-  hipLaunchKernelGGL(k_matrix_update, dim3(1), dim3(TR_MAX_NODES), 0, st, c->d_M, c->V, c->k,
-                     c->tree.n_nodes, d_S, d_topk, c->update_mode);
-  return hipGetLastError();
+  return launch(k_matrix_update, dim3(1), dim3(TR_MAX_NODES), 0, st, KernelTimer{}, c->d_M, c->V, c->k, c->tree.n_nodes,
+                d_S, d_topk, c->update_mode);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -471,29 +472,25 @@ __global__ __launch_bounds__(256) void k_sample_tokens(const float *__restrict__
   if (threadIdx.x == 0) tokens[i] = si[0];
 }
 
-hipError_t launch_sample_tokens(const tr_ctx *c, const tr_kv *kv, const float *d_logits, const float *d_noise,
+hipError_t launch_sample_tokens(tr_ctx *c, const tr_kv *kv, const float *d_logits, const float *d_noise,
                                 int32_t pos0, int32_t noise_rows, float inv_t, int32_t *d_tokens, hipStream_t st) {
-  hipLaunchKernelGGL(k_sample_tokens, dim3(c->tree.n_nodes), dim3(256), 0, st, d_logits, d_noise, c->V, pos0, noise_rows,
-                     inv_t, c->tree.depth, kv->d_len, d_tokens);
-  return hipGetLastError();
+  return launch(k_sample_tokens, dim3(c->tree.n_nodes), dim3(256), 0, st, c->prof.next(PC_SAMPLE), d_logits, d_noise, c->V,
+                pos0, noise_rows, inv_t, c->tree.depth, kv->d_len, d_tokens);
 }
 
-hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t *d_S, const int32_t *d_topk,
+hipError_t launch_accept_update(tr_ctx *c, const tr_kv *kv, const int32_t *d_S, const int32_t *d_topk,
                                 const int32_t *d_tokens, tr_step_out *d_out, hipStream_t st) {
-  hipLaunchKernelGGL(k_accept_update, dim3(1), dim3(TR_MAX_NODES), 0, st, c->d_M, c->V, c->k, c->tree, d_S,
-                     d_topk, d_tokens, kv->d_len, c->d_step_L, d_out, c->update_mode);
-  hipError_t e = hipGetLastError();
+  hipError_t e = launch(k_accept_update, dim3(1), dim3(TR_MAX_NODES), 0, st, c->prof.next(PC_ACCEPT), c->d_M, c->V, c->k,
+                        c->tree, d_S, d_topk, d_tokens, kv->d_len, c->d_step_L, d_out, c->update_mode);
   if (e != hipSuccess) return e;
   const int blocks = kv->n_layers * kv->n_kv_heads;
   const size_t esz = dtype_size(kv->dtype);
   const size_t smem = 2 * (size_t)TR_MAX_LAYERS * kv->head_dim * esz;
   if (kv->dtype == TR_BF16)
-    hipLaunchKernelGGL(k_compact_kv<bf16_t>, dim3(blocks), dim3(256), smem, st, (bf16_t *)kv->k, (bf16_t *)kv->v,
-                       kv->capacity, kv->head_dim, kv->layout, c->d_step_L, d_out);
-  else
-    hipLaunchKernelGGL(k_compact_kv<float>, dim3(blocks), dim3(256), smem, st, (float *)kv->k, (float *)kv->v,
-                       kv->capacity, kv->head_dim, kv->layout, c->d_step_L, d_out);
-  return hipGetLastError();
+    return launch(k_compact_kv<bf16_t>, dim3(blocks), dim3(256), smem, st, c->prof.next(PC_COMPACT), (bf16_t *)kv->k,
+                  (bf16_t *)kv->v, kv->capacity, kv->head_dim, kv->layout, c->d_step_L, d_out);
+  return launch(k_compact_kv<float>, dim3(blocks), dim3(256), smem, st, c->prof.next(PC_COMPACT), (float *)kv->k,
+                (float *)kv->v, kv->capacity, kv->head_dim, kv->layout, c->d_step_L, d_out);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -527,17 +524,14 @@ __global__ __launch_bounds__(512) void k_stream_copy(const u32x4s *__restrict__ 
 hipError_t launch_stream(const void *src, void *dst, size_t bytes, hipStream_t st) {
   const size_t slots = bytes / 16;
   if (dst == nullptr)
-    hipLaunchKernelGGL(k_stream_read, dim3(256), dim3(512), 0, st, (const u32x4s *)src, slots, (uint32_t *)nullptr);
-  else
-    hipLaunchKernelGGL(k_stream_copy, dim3(256), dim3(512), 0, st, (const u32x4s *)src, (u32x4s *)dst, slots);
-  return hipGetLastError();
+    return launch(k_stream_read, dim3(256), dim3(512), 0, st, KernelTimer{}, (const u32x4s *)src, slots, (uint32_t *)nullptr);
+  return launch(k_stream_copy, dim3(256), dim3(512), 0, st, KernelTimer{}, (const u32x4s *)src, (u32x4s *)dst, slots);
 }
 
 __global__ void k_advance_len(int32_t *d_len, int32_t by) { *d_len += by; }
 
 hipError_t launch_advance_len(int32_t *d_len, int32_t by, hipStream_t st) {
-  hipLaunchKernelGGL(k_advance_len, dim3(1), dim3(1), 0, st, d_len, by);
-  return hipGetLastError();
+  return launch(k_advance_len, dim3(1), dim3(1), 0, st, KernelTimer{}, d_len, by);
 }
 
 } // namespace tr

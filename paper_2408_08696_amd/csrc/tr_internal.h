@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -86,32 +87,45 @@ constexpr int GEMM_MAX_SPLITS = 4;
 Workspace plan_workspace(const tr_model &m);
 
 // ---------------------------------------------------------------------------------------------
-// optional per-kernel-class event timing
+// optional per-kernel timing.  While enabled, every kernel of the step is launched with a start and a
+// stop event attached to the dispatch itself (hipExtLaunchKernelGGL), so the elapsed time between the
+// two is the kernel's own duration, without the launch latency an event pair recorded around a launch
+// would include.
 // ---------------------------------------------------------------------------------------------
-enum ProfCat { PC_BUILD = 0, PC_EMBED, PC_NORM, PC_QKV, PC_ROPE, PC_ATTN, PC_OPROJ, PC_GATEUP, PC_DOWN, PC_LMHEAD,
-               PC_TOPK, PC_ACCEPT, PC_EMPTY, PC_COUNT };
+enum ProfCat { PC_BUILD = 0, PC_EMBED, PC_NORM, PC_QKV, PC_ROPE, PC_ATTN, PC_ATTN_MERGE, PC_OPROJ, PC_GATEUP, PC_DOWN,
+               PC_LMHEAD, PC_TOPK, PC_TOPK_MERGE, PC_ACCEPT, PC_COMPACT, PC_SAMPLE, PC_COUNT };
+struct KernelTimer {
+  hipEvent_t start = nullptr, stop = nullptr; // both null: launch untimed
+};
 struct Profiler {
   static constexpr int MAX_PAIRS = 8192;
   hipEvent_t *ev = nullptr; // 2 * MAX_PAIRS
   int8_t *cat = nullptr;    // MAX_PAIRS
   int used = 0;
   bool enabled = false;
-};
-struct ProfScope {
-  Profiler *p;
-  hipStream_t st;
-  int slot;
-  ProfScope(Profiler *prof, ProfCat c, hipStream_t s) : p(prof), st(s), slot(-1) {
-    if (p != nullptr && p->enabled && p->used < Profiler::MAX_PAIRS) {
-      slot = p->used++;
-      p->cat[slot] = (int8_t)c;
-      (void)hipEventRecord(p->ev[2 * slot], st);
+  KernelTimer next(ProfCat c) {
+    KernelTimer t;
+    if (enabled && used < MAX_PAIRS) {
+      cat[used] = (int8_t)c;
+      t.start = ev[2 * used];
+      t.stop = ev[2 * used + 1];
+      ++used;
     }
-  }
-  ~ProfScope() {
-    if (slot >= 0) (void)hipEventRecord(p->ev[2 * slot + 1], st);
+    return t;
   }
 };
+inline KernelTimer prof_next(Profiler *p, ProfCat c) { return p != nullptr ? p->next(c) : KernelTimer{}; }
+
+// One place through which every kernel of the library is launched.
+template <typename... KArgs, typename... Args>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t smem, hipStream_t st, KernelTimer t,
+                         Args... args) {
+  if (t.start != nullptr)
+    hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)smem, st, t.start, t.stop, 0u, static_cast<KArgs>(args)...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, smem, st, static_cast<KArgs>(args)...);
+  return hipGetLastError();
+}
 
 } // namespace tr
 
@@ -131,10 +145,10 @@ struct tr_ctx {
 namespace tr {
 
 // --- integer kernels (tr_int_kernels.hip) -------------------------------------------------------
-hipError_t launch_build_tree(const tr_ctx *c, const int32_t *d_root, int32_t *d_S, hipStream_t s);
+hipError_t launch_build_tree(tr_ctx *c, const int32_t *d_root, int32_t *d_S, hipStream_t s);
 // d_cand: scratch of topk_scratch_bytes() owned by the context (may be NULL: slower one-kernel path)
 hipError_t launch_topk(const void *logits, int32_t dtype, int32_t rows, int32_t V, int32_t k,
-                       int32_t *d_topk, void *d_cand, hipStream_t s);
+                       int32_t *d_topk, void *d_cand, Profiler *prof, hipStream_t s);
 size_t topk_scratch_bytes();
 // the same two-stage kernels on the library's static device scratch (no allocation anywhere)
 bool topk_static_fits(int32_t rows, int32_t V, int32_t k);
@@ -142,9 +156,9 @@ hipError_t launch_topk_static(const void *logits, int32_t dtype, int32_t rows, i
                               int32_t *d_topk, hipStream_t s);
 hipError_t launch_matrix_update(const tr_ctx *c, const int32_t *d_S, const int32_t *d_topk, hipStream_t s);
 // d_tokens: the model's token per node, or NULL for the argmax (first top-k column)
-hipError_t launch_accept_update(const tr_ctx *c, const tr_kv *kv, const int32_t *d_S,
+hipError_t launch_accept_update(tr_ctx *c, const tr_kv *kv, const int32_t *d_S,
                                 const int32_t *d_topk, const int32_t *d_tokens, tr_step_out *d_out, hipStream_t s);
-hipError_t launch_sample_tokens(const tr_ctx *c, const tr_kv *kv, const float *d_logits, const float *d_noise,
+hipError_t launch_sample_tokens(tr_ctx *c, const tr_kv *kv, const float *d_logits, const float *d_noise,
                                 int32_t pos0, int32_t noise_rows, float inv_t, int32_t *d_tokens, hipStream_t s);
 hipError_t launch_advance_len(int32_t *d_len, int32_t by, hipStream_t s);
 hipError_t launch_stream(const void *src, void *dst, size_t bytes, hipStream_t s);

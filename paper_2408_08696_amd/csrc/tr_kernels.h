@@ -81,7 +81,7 @@ inline void gemm_plan(GemmArgs &g, int32_t max_splits) {
 }
 
 bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O);
-hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st);
+hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st, KernelTimer tm = KernelTimer{});
 // rope_hd > 0: packed row h*rope_hd + 2j + b takes source row h*rope_hd + j + b*rope_hd/2 (query / key
 // matrices: the two features of a rotation pair become neighbours)
 hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t K, int32_t rope_hd, hipStream_t st);
@@ -94,6 +94,6 @@ int attn_heads_per_wg(int32_t H, int32_t Hkv, int32_t n);
 int attn_choose_splits(int32_t head_groups, int32_t len_bound);
 hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                             int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t len_bound, float *part_ml,
-                            float *part_acc, bf16_t *out, int32_t out_row_tiles, hipStream_t st);
+                            float *part_acc, bf16_t *out, int32_t out_row_tiles, Profiler *prof, hipStream_t st);
 
 } // namespace tr

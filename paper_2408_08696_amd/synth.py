@@ -346,7 +346,47 @@ def prefix_template(n: int) -> TreeTemplate:
     return TreeTemplate(f"prefix{n}", parent, rank, len(sizes), sizes)
 
 
+# 80-row templates of 4..8 layers for the depth sweep (the paper's Figure 3b fixes the node count at 80
+# and varies the depth; its trees are not given, so these keep 8 children at the root, layer widths that
+# fall off with depth, and more children for the earlier nodes of a layer, like tree80)
+_DEPTH_LAYER_SIZES = {
+    4: (1, 8, 28, 43),
+    5: (1, 8, 24, 28, 19),
+    6: (1, 8, 21, 25, 15, 10),
+    7: (1, 8, 18, 20, 15, 10, 8),
+    8: (1, 8, 16, 18, 13, 10, 8, 6),
+}
+
+
+def _spread_children(n_parents: int, n_children: int, k: int) -> List[int]:
+    """Child counts for one layer: dealt one at a time to the parent with the largest share still owed,
+    shares proportional to 1/(i+1) (earlier parents first on ties), at most k per parent."""
+    assert n_children <= n_parents * k
+    w = np.array([1.0 / (i + 1) for i in range(n_parents)])
+    w = w / w.sum() * n_children
+    c = [0] * n_parents
+    for _ in range(n_children):
+        owed = [(w[i] - c[i]) if c[i] < k else -1e9 for i in range(n_parents)]
+        i = int(np.argmax(owed))
+        c[i] += 1
+    return c
+
+
+def depth_template(n_layers: int, k: int = 8) -> TreeTemplate:
+    """80 rows in n_layers layers (4..8); the 6-layer one is tree80 itself."""
+    if n_layers == 6:
+        t = tree80()
+        return TreeTemplate("depth6", t.parent, t.rank, t.n_layers, t.layer_sizes)
+    sizes = _DEPTH_LAYER_SIZES[n_layers]
+    counts = [_spread_children(sizes[d], sizes[d + 1], k) for d in range(n_layers - 1)]
+    t = template_from_child_counts(f"depth{n_layers}", counts)
+    assert t.n_nodes == 80 and t.n_layers == n_layers, (t.n_nodes, t.n_layers)
+    return t
+
+
 TEMPLATES = {
     "tree80": tree80, "tree81": tree81, "tree15": tree15, "tree15_alt": tree15_alt,
     "single": single, "wide128": wide128,
+    "depth4": lambda: depth_template(4), "depth5": lambda: depth_template(5), "depth7": lambda: depth_template(7),
+    "depth8": lambda: depth_template(8),
 }

@@ -67,6 +67,9 @@ def test_tiny_fp32_free_running(tmpl_name):
                                                   ("tiny_bf16", "single"), ("tiny", "tree80"),
                                                   ("tiny_odd_bf16", "tree80"), ("tiny_bf16:rowmajor", "tree15"),
                                                   ("tiny_bf16", "prefix48"), ("tiny_gqa_bf16", "prefix97"),
+                                                  # the depth sweep's 80-node templates of 4, 5, 7 and 8 layers
+                                                  ("tiny_bf16", "depth4"), ("tiny_bf16", "depth5"),
+                                                  ("tiny_gqa_bf16", "depth7"), ("tiny_bf16", "depth8"),
                                                   ("tiny_hd64_bf16", "tree80"), ("tiny_gqa_bf16:plainkv", "tree80"),
                                                   # projection-kernel variants of the full-size models
                                                   ("zoo_ffn5504", "tree80"), ("zoo_ffn5504", "tree81"),

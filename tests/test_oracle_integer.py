@@ -35,7 +35,8 @@ def _walk(M, parent, rank, root, n):
     return int(M[_walk(M, parent, rank, root, parent[n])][rank[n]])
 
 
-@pytest.mark.parametrize("name", ["tree80", "tree81", "tree15", "tree15_alt", "wide128", "single"])
+@pytest.mark.parametrize("name", ["tree80", "tree81", "tree15", "tree15_alt", "wide128", "single", "depth4", "depth5",
+                                  "depth7", "depth8"])
 def test_build_tree_equals_path_walk(name):
     t = synth.TEMPLATES[name]()
     rng = np.random.default_rng(1)
@@ -70,6 +71,24 @@ def test_default_template_sizes(golden):
         O.make_tree(t.parent, t.rank, k)                    # well-formed
     rows = int(g["matrix_rows"][0][0])
     assert round(rows * k * 8 / 2 ** 20, 2) == float(g["matrix_mib_at_8_bytes"][0][0])
+
+
+def test_depth_sweep_templates_keep_80_rows():
+    """Section 5.1 varies the depth at a fixed 80 nodes: the sweep's templates have 80 rows, the asked
+    number of layers, at most k children per node, and a first-child chain that reaches the last layer
+    (so a step can accept depth - 1 drafts)."""
+    for D in (4, 5, 6, 7, 8):
+        t = synth.depth_template(D)
+        tree = O.make_tree(t.parent, t.rank, 8)
+        assert t.n_nodes == 80 and t.n_layers == D == tree.n_layers and sum(t.layer_sizes) == 80
+        assert np.bincount(t.parent[1:], minlength=80).max() <= 8
+        n, hops = 0, 0
+        while True:
+            kids = [c for c in range(80) if t.parent[c] == n and t.rank[c] == 0]
+            if not kids:
+                break
+            n, hops = kids[0], hops + 1
+        assert hops == D - 1
 
 
 def test_make_tree_rejects_malformed():
@@ -128,7 +147,7 @@ def _brute_accept(S, out, parent):
     return best
 
 
-@pytest.mark.parametrize("name", ["tree80", "tree15", "tree15_alt", "wide128"])
+@pytest.mark.parametrize("name", ["tree80", "tree15", "tree15_alt", "wide128", "depth4", "depth8"])
 def test_accept_equals_brute_force_over_leaf_paths(name):
     t = synth.TEMPLATES[name]()
     tree = O.make_tree(t.parent, t.rank, 8)
