@@ -215,7 +215,9 @@ tr_status tr_plan_projection(int32_t n_rows, int32_t in_f, int32_t out_f, int32_
  * Launch plan of the tree-attention kernel (Section 2.2 "Tree Attention") for n_heads query heads over
  * n_kv_heads K/V heads, n_nodes tree nodes and a host bound len_bound on committed length + tree nodes
  * (diagnostic; touches no GPU): plan[0] = query heads one workgroup serves (heads sharing a K/V head
- * share its staged tiles), plan[1] = key-axis splits.  plan is [host], 2 values.  TR_EINVAL for null
+ * share its staged tiles), plan[1] = key-axis splits, or 0 for the one-launch form short sequences take (one
+ * workgroup per query head and tile of 16 nodes, its waves splitting the keys, no merge pass).  plan is
+ * [host], 2 values.  TR_EINVAL for null
  * plan, n_kv_heads < 1, n_heads not a positive multiple of n_kv_heads, n_nodes outside 1..TR_MAX_NODES
  * or len_bound < 1.
  */

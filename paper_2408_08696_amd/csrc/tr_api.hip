@@ -217,6 +217,11 @@ tr_status tr_plan_attention(int32_t n_heads, int32_t n_kv_heads, int32_t n_nodes
   if (plan == nullptr || n_kv_heads < 1 || n_heads < n_kv_heads || n_heads % n_kv_heads != 0 || n_nodes < 1 ||
       n_nodes > TR_MAX_NODES || len_bound < 1)
     return TR_EINVAL;
+  if (attn_one_launch(n_heads, n_kv_heads, len_bound)) { // one workgroup per (head, node tile), no key splits
+    plan[0] = 1;
+    plan[1] = 0;
+    return TR_OK;
+  }
   plan[0] = attn_heads_per_wg(n_heads, n_kv_heads, n_nodes);
   plan[1] = attn_choose_splits(n_heads / plan[0], len_bound);
   return TR_OK;

@@ -245,6 +245,158 @@ __global__ __launch_bounds__(NT * HPW * 64) void k_attn_mfma(const bf16_t *__res
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// One-launch form for short sequences: a workgroup owns one (query head, tile of 16 nodes) and its eight
+// waves split the keys (wave w takes the 32-key tiles w, w+8, ...), each reading its K/V tiles from memory
+// straight into matrix-core operand registers (the cache layout is that order; nothing is shared between the
+// waves, so nothing is staged).  The waves' (max, sum, accumulator) meet in LDS and wave w finishes features
+// 16w .. 16w+15 of all 16 nodes, so no partial result ever leaves the compute unit and no merge launch
+// follows.  The node tiles of a head read the same K/V: their workgroups are numbered so that round-robin
+// placement puts them on one XCD, whose L2 serves the repeats.  Every compute unit then pulls the whole
+// sequence of its head, (L + N) * 512 bytes, which is why this form is only chosen for short sequences.
+// ---------------------------------------------------------------------------------------------
+constexpr int ATT1_WAVES = 8;
+constexpr size_t ATT1_LDS_BYTES = (size_t)ATT1_WAVES * 8 * 64 * 16 + (size_t)ATT1_WAVES * 16 * 2 * 4;
+template <int DUMMY>
+__global__ __launch_bounds__(ATT1_WAVES * 64) void k_attn_tile(const bf16_t *__restrict__ q, const bf16_t *__restrict__ Kl,
+                                                             const bf16_t *__restrict__ Vl, int32_t H, int32_t Hkv,
+                                                             int32_t cap, int32_t n, int32_t NT,
+                                                             const uint64_t *__restrict__ anc,
+                                                             const int32_t *__restrict__ d_len, bf16_t *__restrict__ out,
+                                                             int32_t out_row_tiles) {
+  extern __shared__ f32x4 att1_lds[]; // ATT1_LDS_BYTES
+  f32x4 (*s_acc)[8][64] = reinterpret_cast<f32x4 (*)[8][64]>(att1_lds);                         // [waves][8][64], 64 KiB
+  float (*s_ml)[16][2] = reinterpret_cast<float (*)[16][2]>(att1_lds + ATT1_WAVES * 8 * 64);    // [waves][16][2]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int r = lane & 15, g = lane >> 4;
+  // linear id -> (head, node tile): ids that differ by 8 share a head's XCD; x = id % 8 picks the head inside
+  // a block of 8 heads, y = id / 8 runs over (node tile, head block)
+  const int id = blockIdx.x, x8 = id & 7, y = id >> 3;
+  const int wt = y % NT, h = (y / NT) * 8 + x8;
+  if (h >= H) return; // uniform over the workgroup (H not a multiple of 8)
+  const int hk = h / (H / Hkv);
+
+  const int node = wt * 16 + r;
+  const int node_c = node < n ? node : n - 1;
+  u32x4 qf[4];
+  {
+    const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + ((size_t)node_c * H + h) * 128 + 8 * g);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) qf[c] = qp[c * 4];
+  }
+  const uint64_t a0 = anc[2 * node_c], a1 = anc[2 * node_c + 1];
+  const u32x4 *Kh = reinterpret_cast<const u32x4 *>(Kl + (size_t)hk * cap * 128) + lane;
+  const u32x4 *Vh = reinterpret_cast<const u32x4 *>(Vl + (size_t)hk * cap * 128) + lane;
+
+  f32x4 acc[8];
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  f32x4 accl = f32x4{0.f, 0.f, 0.f, 0.f};
+  const u32x4 ones = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  float m = NEG_BIG;
+  const float sc = 0.08838834764831845f * 1.4426950408889634f; // 1/sqrt(128) * log2(e)
+
+  u32x4 kq[2][8], vq[2][8]; // two tiles of operands in registers: the one in use and the next
+  auto fetch = [&](int buf, int tile) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) kq[buf][c] = __builtin_nontemporal_load(Kh + (size_t)tile * 512 + c * 64);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) vq[buf][c] = __builtin_nontemporal_load(Vh + (size_t)tile * 512 + c * 64);
+  };
+  if ((wave + 1) * 32 <= cap) fetch(0, wave); // inside the allocation even if beyond the sequence
+  const int L = *d_len;
+  const int total = L + n;
+  const int n_tiles = (total + 31) >> 5;
+  int i = 0;
+  for (int t = wave; t < n_tiles; t += ATT1_WAVES, ++i) {
+    const bool has_next = t + ATT1_WAVES < n_tiles;
+    // the buffers alternate by compile-time index: two copies of the body
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      if ((i & 1) != b) continue;
+      if (has_next) fetch(b ^ 1, t + ATT1_WAVES);
+      f32x4 s0 = f32x4{0.f, 0.f, 0.f, 0.f}, s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        s0 = mfma16a(kq[b][c], qf[c], s0);
+        s1 = mfma16a(kq[b][4 + c], qf[c], s1);
+      }
+      float xs[8];
+      bool vis[8];
+      const bool in_prefix = t * 32 + 32 <= L; // uniform: every key of the tile is visible to every node
+      const int pbase = t * 32 + 4 * g;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int p = pbase + (e >> 2) * 16 + (e & 3);
+        bool v = in_prefix || p < L;
+        if (!v && p < total) {
+          const int j = p - L;
+          v = j < 64 ? ((a0 >> j) & 1ull) : ((a1 >> (j - 64)) & 1ull);
+        }
+        vis[e] = v;
+        const float sv = (e < 4 ? s0[e & 3] : s1[e & 3]) * sc;
+        xs[e] = v ? sv : NEG_BIG;
+      }
+      float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m, mx);
+      if (__any(m_new > m)) {
+        const float corr = __builtin_amdgcn_exp2f(m - m_new);
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          acc[dt][0] *= corr; acc[dt][1] *= corr; acc[dt][2] *= corr; acc[dt][3] *= corr;
+        }
+        accl[0] *= corr; accl[1] *= corr; accl[2] *= corr; accl[3] *= corr;
+        m = m_new;
+      }
+      float pr[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pr[e] = vis[e] ? __builtin_amdgcn_exp2f(xs[e] - m) : 0.f;
+      u32x4 pf;
+#pragma unroll
+      for (int e = 0; e < 8; e += 2)
+        pf[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pr[e], pr[e + 1]}, bf16x2));
+      accl = mfma16a(ones, pf, accl);
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) acc[dt] = mfma16a(vq[b][dt], pf, acc[dt]);
+    }
+  }
+
+  // meet in LDS: every wave leaves its accumulators (unnormalised), its running maximum and its sum
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) s_acc[wave][dt][lane] = acc[dt];
+  if (g == 0) {
+    s_ml[wave][r][0] = m;
+    s_ml[wave][r][1] = accl[0];
+  }
+  __syncthreads();
+  // wave w finishes features 16w .. 16w+15: out = sum_v acc_v 2^(m_v - M) / sum_v l_v 2^(m_v - M) in wave order
+  float M = NEG_BIG;
+#pragma unroll
+  for (int v = 0; v < ATT1_WAVES; ++v)
+    if (s_ml[v][r][1] > 0.f) M = fmaxf(M, s_ml[v][r][0]);
+  float den = 0.f;
+  f32x4 num = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int v = 0; v < ATT1_WAVES; ++v) {
+    const float lv = s_ml[v][r][1];
+    if (lv > 0.f) {
+      const float w = __builtin_amdgcn_exp2f(s_ml[v][r][0] - M);
+      den += w * lv;
+      num += s_acc[v][wave][lane] * w;
+    }
+  }
+  if (node >= n) return;
+  const float inv = 1.0f / den;
+  const int d = 16 * wave + 4 * g;
+  ushort4 o;
+  o.x = f32_to_bf16(num[0] * inv); o.y = f32_to_bf16(num[1] * inv);
+  o.z = f32_to_bf16(num[2] * inv); o.w = f32_to_bf16(num[3] * inv);
+  const size_t idx = out_row_tiles > 0 ? act_frag_index(node, h * 128 + d, out_row_tiles) : ((size_t)node * H + h) * 128 + d;
+  store_stream(out + idx, o);
+}
+
 // out[node, h, :] = sum_s w_s o_s / sum_s w_s with w_s = l_s 2^(m_s - max m), o_s the split's normalised
 // output; splits without visible keys (l_s == 0) contribute nothing.  Block (8 nodes, head), 32 threads x
 // 4 features per node; all loads of a thread are issued before any arithmetic.
@@ -323,11 +475,27 @@ static hipError_t launch_attn_nt(int hpw, const bf16_t *q, const bf16_t *Kl, con
   return launch_attn_k<NT, 1>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st);
 }
 
+// The one-launch form pays when a compute unit can pull its head's whole sequence in less time than the
+// split form spends on its second launch: up to about this many positions (prefix + nodes), and only when few
+// query heads share a K/V head (each of them re-reads it).  Measured at 32 heads, 80 nodes (us per layer, one
+// launch / split + merge): 7.8 / 11.0 at 256 positions, 10.3 / 12.5 at 512, 12.5 / 13.3 at 768, 14.5 / 14.2
+// at 1024, 22.2 / 17.9 at 2048.
+constexpr int ATT1_MAX_LEN = 832;
+bool attn_one_launch(int32_t H, int32_t Hkv, int32_t len_bound) { return len_bound <= ATT1_MAX_LEN && H / Hkv <= 2; }
+
 hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                             int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t len_bound, float *part_ml,
                             float *part_acc, bf16_t *out, int32_t out_row_tiles, Profiler *prof, hipStream_t st) {
   if (Hkv < 1 || H % Hkv != 0) return hipErrorInvalidValue;
   const KernelTimer tm = prof_next(prof, PC_ATTN);
+  if (attn_one_launch(H, Hkv, len_bound)) {
+    const int NT = (n + 15) / 16;
+    static bool once = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_attn_tile<0>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)ATT1_LDS_BYTES) == hipSuccess;
+    if (!once) return hipErrorInvalidValue;
+    return launch(k_attn_tile<0>, dim3(((H + 7) / 8) * 8 * NT), dim3(ATT1_WAVES * 64), ATT1_LDS_BYTES, st, tm, q, Kl, Vl,
+                  H, Hkv, cap, n, NT, anc, d_len, out, out_row_tiles);
+  }
   const int hpw = attn_heads_per_wg(H, Hkv, n);
   const int nsplit = attn_choose_splits(H / hpw, len_bound);
   hipError_t e = hipErrorInvalidValue;

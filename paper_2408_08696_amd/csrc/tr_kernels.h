@@ -92,6 +92,8 @@ hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t
 // uses for H / that many head groups and this bound on committed length + nodes.
 int attn_heads_per_wg(int32_t H, int32_t Hkv, int32_t n);
 int attn_choose_splits(int32_t head_groups, int32_t len_bound);
+// true: one launch without key splits or merge pass (short sequences); then the two values above do not apply
+bool attn_one_launch(int32_t H, int32_t Hkv, int32_t len_bound);
 hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                             int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t len_bound, float *part_ml,
                             float *part_acc, bf16_t *out, int32_t out_row_tiles, Profiler *prof, hipStream_t st);

@@ -146,6 +146,9 @@ def test_attention_plan(lib):
             prev = 1
             for L in (1, 31, 32, 33, 64, 100, 600, 2048, 8192, 65536):
                 hpw, ns = tr.plan_attention(H, Hkv, n, L)
+                if ns == 0:                                           # one-launch form: short sequences only
+                    assert hpw == 1 and L <= 832 and H // Hkv <= 2 and prev <= 1
+                    continue
                 assert hpw in (1, 2) and (H // Hkv) % hpw == 0       # heads of one workgroup share a K/V head
                 assert ((n + 15) // 16) * hpw <= (12 if hpw == 2 else 8)   # one wave per (head, node tile)
                 groups = H // hpw
@@ -154,7 +157,9 @@ def test_attention_plan(lib):
                 assert ns == 1 or groups * ns <= 256                  # at most one workgroup per CU
                 assert ns >= prev                                     # never fewer splits for a longer context
                 prev = ns
-    assert tr.plan_attention(32, 32, 80, 600) == (1, 8)
+    assert tr.plan_attention(32, 32, 80, 600) == (1, 0)
+    assert tr.plan_attention(32, 32, 80, 1104) == (1, 8)
+    assert tr.plan_attention(64, 8, 80, 600)[1] >= 1                      # eight query heads per K/V head: split form
     assert tr.plan_attention(40, 40, 80, 2128) == (1, 6)
     assert tr.plan_attention(64, 8, 80, 4176)[0] == 2
 
