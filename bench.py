@@ -128,9 +128,17 @@ def attention_microbench(sh, tmpl, torch, tr, L=1024, reps=5):
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / (reps * sh.n_layers)
     nbytes = (L + n) * sh.n_kv_heads * hd * 2 * 2 + 2 * n * H * hd * 2    # K, V, Q, O
-    return {"workload": f"H={H} Hkv={sh.n_kv_heads} hd={hd} L={L} N={n}, bf16, {sh.n_layers} rotating cache layers",
-            "us_per_layer": us, "algorithmic_bytes_per_layer": nbytes, "achieved_GBs": nbytes / us * 1e-3,
-            "frac_of_peak_hbm": nbytes / us * 1e-3 / PEAK_HBM_GBS}
+    res = {"workload": f"H={H} Hkv={sh.n_kv_heads} hd={hd} L={L} N={n}, bf16, {sh.n_layers} rotating cache layers",
+           "us_per_layer": us, "algorithmic_bytes_per_layer": nbytes, "achieved_GBs": nbytes / us * 1e-3,
+           "frac_of_peak_hbm": nbytes / us * 1e-3 / PEAK_HBM_GBS, "traffic": None}
+    # HBM bytes per layer from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, if a summary for this shape is recorded
+    pmc = os.path.join(ROOT, "profiles", f"tree_attention_L{L}_pmc.txt")
+    if H == 32 and sh.n_kv_heads == 32 and n == 80 and os.path.exists(pmc):
+        for line in open(pmc):
+            if line.startswith("traffic_bytes_per_layer:"):
+                res["traffic"] = float(line.split(":")[1])
+                res["traffic_source"] = os.path.relpath(pmc, ROOT)
+    return res
 
 
 def main():
@@ -162,6 +170,12 @@ def main():
                                  tr.plan_attention(sh.n_heads, sh.n_kv_heads, tmpl.n_nodes, L + tmpl.n_nodes)))
             rows.append(r)
             say(f"L={L}: {r['us_per_layer']:.2f} us per layer")
+        if a.calibrate_copy:
+            # a copy of known size (256 MiB read + 256 MiB written) for calibrating rocprofv3 --pmc byte counters
+            src, dst = (torch.ones(1 << 26, dtype=torch.float32, device="cuda") for _ in range(2))
+            for _ in range(4):
+                tr.op_stream(src, dst)
+            torch.cuda.synchronize()
         print(json.dumps({"metric": "tree attention time vs prefix length", "unit": "us/layer", "n_gpus": 1,
                           "dtype": "bf16", "data": "synthetic",
                           "config": {"workload": f"{sh.name}-shape heads (H={sh.n_heads}, Hkv={sh.n_kv_heads}, hd="
