@@ -45,6 +45,8 @@ def parse():
                     help="comma-separated tree depths (layers including the root, 4..8): time the step for 80-node "
                          "templates of each depth instead of the headline run, cold and with the hot-start matrix "
                          "the cold run leaves, and print one JSON line with the table")
+    ap.add_argument("--sweep-prefill", default="",
+                    help="comma-separated prompt lengths: time prompt ingestion (tr_prefill) at each, print one JSON line")
     ap.add_argument("--sweep-attention", default="",
                     help="comma-separated prefix lengths: time the tree-attention op alone (attention kernel + split "
                          "merge, the shape's heads, 80-node tree, rotating cache layers) at each, instead of the "
@@ -208,6 +210,33 @@ def main():
     total_steps = a.warmup + a.steps + a.profile_steps
     cap = a.prompt_len + total_steps * tmpl.n_layers + tmpl.n_nodes + 64
 
+    if a.sweep_prefill:
+        # Prompt ingestion alone: len - 1 tokens through tr_prefill (the last prompt token is the first root),
+        # average of --steps repetitions after one untimed call.
+        if model is None:
+            model = tr.ModelDesc(sh, w)
+        del w
+        lens = [int(v) for v in a.sweep_prefill.split(",")]
+        e = tr.Engine(sh, None, tmpl, k=K, capacity=max(lens) + 256, keep_logits=False, model=model)
+        rows = []
+        for pl in lens:
+            p = synth.zipf_prompt(sh.vocab, pl, seed=0, ngram=8).tolist()
+            e.prefill(p)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(a.steps):
+                e.prefill(p)
+            torch.cuda.synchronize()
+            dtp = (time.perf_counter() - t0) / a.steps
+            rows.append({"prompt_tokens": pl - 1, "ms": dtp * 1e3, "tokens_per_s": (pl - 1) / dtp,
+                         "weight_reads": -(-(pl - 1) // 512)})
+            say(rows[-1])
+        print(json.dumps({"metric": "prompt ingestion time", "unit": "ms", "n_gpus": 1, "steps": a.steps,
+                          "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": f"{sh.name}-shape random-init Llama bf16, batch 1, Zipf prompts"},
+                          "sweep": rows}))
+        return
+
     if a.sweep_depth:
         # Step time and accepted length versus tree depth at a fixed 80 nodes (Section 5.1 / Figure 3b).  Step
         # time barely moves (the forward sees 80 rows whatever their arrangement); what a deeper tree changes is
@@ -328,7 +357,7 @@ def main():
                    "n_layers": sh.n_layers, "d_model": sh.d_model, "vocab": sh.vocab},
         "tokens_per_s": steps_s * mat, "mat": mat,
         "prefill": {"prompt_tokens": len(prompt) - 1, "ms": prefill_s * 1e3,
-                    "tokens_per_s": (len(prompt) - 1) / prefill_s, "how": "decode kernels in 128-row chunks"},
+                    "tokens_per_s": (len(prompt) - 1) / prefill_s, "how": "passes of up to 512 rows: wide projection kernel, attention per block of 128 rows"},
         "step_roofline": step_roofline, "roofline": roofline,
         "breakdown_ms_per_step": breakdown,
     }

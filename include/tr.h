@@ -33,6 +33,7 @@ extern "C" {
 #endif
 
 #define TR_MAX_NODES 128  /* tree rows including the root                      */
+#define TR_PREFILL_ROWS 512 /* prompt rows one ingestion pass takes (packed models) */
 #define TR_MAX_LAYERS 32  /* tree layers including the root layer              */
 #define TR_MAX_K 32       /* candidates per token (columns of the matrix)      */
 
@@ -312,6 +313,9 @@ tr_status tr_prefill(tr_ctx *ctx, const tr_model *model, tr_kv *kv, const int32_
  *   row-major or packed (layout), both of element type dtype.  With TR_PACKED the call goes through
  *   the kernel the projections use (x is rearranged into the workspace first; `splits` partial sums
  *   over in_f are added up in order); with TR_ROW_MAJOR through the generic kernel (splits ignored).
+ *   n_rows is 1..TR_MAX_NODES; with TR_PACKED up to TR_PREFILL_ROWS, where more than TR_MAX_NODES rows go
+ *   through the kernel that prompt ingestion uses (in_f >= 64; it splits over in_f at most `splits` times,
+ *   fewer when the launch fills the chip without).
  */
 tr_status tr_op_topk(tr_ctx *ctx, const void *d_logits, int32_t dtype, int32_t n_rows,
                      int32_t *d_topk, void *stream);

@@ -302,9 +302,10 @@ tr_status tr_prefill(tr_ctx *c, const tr_model *m, tr_kv *kv, const int32_t *d_t
   if ((int64_t)kv->len_bound + n_tokens > kv->capacity) return TR_ECAPACITY;
   if (ws_bytes < plan_workspace(*m).total) return TR_ECAPACITY;
   hipStream_t st = as_stream(stream);
-  for (int lo = 0; lo < n_tokens; lo += TR_MAX_NODES) {
-    const int n = n_tokens - lo < TR_MAX_NODES ? n_tokens - lo : TR_MAX_NODES;
-    if (run_forward(*m, *kv, c->chain, n, d_tokens + lo, nullptr, ws, nullptr, st) != hipSuccess) return TR_EHIP;
+  const int rows = prefill_rows(*m, *kv);
+  for (int lo = 0; lo < n_tokens; lo += rows) {
+    const int n = n_tokens - lo < rows ? n_tokens - lo : rows;
+    if (run_prefill_pass(*m, *kv, c->chain, n, d_tokens + lo, ws, st) != hipSuccess) return TR_EHIP;
     if (launch_advance_len(kv->d_len, n, st) != hipSuccess) return TR_EHIP;
     kv->len_bound += n;
   }
@@ -353,9 +354,12 @@ tr_status tr_op_linear(tr_ctx *c, const void *d_x, const void *d_w, int32_t dtyp
   if (c == nullptr || d_x == nullptr || d_w == nullptr || d_y == nullptr) return TR_EINVAL;
   if (dtype != TR_F32 && dtype != TR_BF16) return TR_EINVAL;
   if (layout != TR_ROW_MAJOR && layout != TR_PACKED) return TR_EINVAL;
-  if (n_rows <= 0 || n_rows > TR_MAX_NODES || in_f <= 0 || out_f <= 0) return TR_EINVAL;
+  if (n_rows <= 0 || n_rows > (layout == TR_PACKED ? TR_PREFILL_ROWS : TR_MAX_NODES) || in_f <= 0 || out_f <= 0)
+    return TR_EINVAL;
   if (layout == TR_PACKED) {
-    if (dtype != TR_BF16 || !gemm_mfma_supported(n_rows, in_f, out_f)) return TR_EINVAL;
+    if (dtype != TR_BF16) return TR_EINVAL;
+    if (n_rows <= TR_MAX_NODES ? !gemm_mfma_supported(n_rows, in_f, out_f) : !gemm_wide_supported(n_rows, in_f, out_f))
+      return TR_EINVAL;
     if (splits < 1 || splits > GEMM_MAX_SPLITS) return TR_EINVAL;
     if (ws == nullptr || ws_bytes < linear_workspace_bytes(n_rows, in_f, out_f, splits)) return TR_ECAPACITY;
   }

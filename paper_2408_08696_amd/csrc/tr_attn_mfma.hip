@@ -46,7 +46,7 @@ __global__ __launch_bounds__(NT * HPW * 64) void k_attn_mfma(const bf16_t *__res
                                                        int32_t cap, int32_t n, const uint64_t *__restrict__ anc,
                                                        const int32_t *__restrict__ d_len, int32_t nsplit,
                                                        float *__restrict__ part_ml, float *__restrict__ part_acc,
-                                                       bf16_t *__restrict__ out, int32_t out_row_tiles) {
+                                                       bf16_t *__restrict__ out, int32_t out_row_tiles, int32_t row0) {
   constexpr int THREADS = NT * HPW * 64;
   constexpr int SLOTS = ATT_TILE_BYTES / 16;                 // 16-byte slots per tile
   constexpr int PER_THREAD = (SLOTS + THREADS - 1) / THREADS;
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(NT * HPW * 64) void k_attn_mfma(const bf16_t *__res
   // exponent with one fma, the accumulators are rescaled only when some lane's maximum moved, and the
   // bf16 rounding of the probabilities is the hardware's packed conversion.
   if ((split + 1) * 32 <= cap) fetch(split); // inside the cache allocation even if beyond the sequence
-  const int L = *d_len;
+  const int L = *d_len + row0;
   const int total = L + n;
   const int n_tiles = (total + 31) >> 5;
   int buf = 0;
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(NT * HPW * 64) void k_attn_mfma(const bf16_t *__res
       ushort4 o;
       o.x = f32_to_bf16(acc[dt][0] * inv); o.y = f32_to_bf16(acc[dt][1] * inv);
       o.z = f32_to_bf16(acc[dt][2] * inv); o.w = f32_to_bf16(acc[dt][3] * inv);
-      const size_t idx = out_row_tiles > 0 ? act_frag_index(node, h * 128 + d, out_row_tiles)
+      const size_t idx = out_row_tiles > 0 ? act_frag_index(node + row0, h * 128 + d, out_row_tiles)
                                            : ((size_t)node * H + h) * 128 + d;
       store_stream(out + idx, o);
     }
@@ -215,10 +215,10 @@ __global__ __launch_bounds__(NT * HPW * 64) void k_attn_mfma(const bf16_t *__res
   // a split's partial result is its own normalised output (a convex combination of V rows, so it fits
   // half precision with 2^-11 relative error, below the bf16 rounding of the merged output) plus (m, l).
   // The wave's 16 x 128 block is turned through LDS so that a node's 256 bytes leave as whole lines.
-  const size_t row0 = ((size_t)split * H + h) * NP + wt * 16;
+  const size_t prow = ((size_t)split * H + h) * NP + wt * 16;
   if (g == 0 && node < n) {
-    part_ml[(row0 + r) * 2] = m;
-    part_ml[(row0 + r) * 2 + 1] = lsum;
+    part_ml[(prow + r) * 2] = m;
+    part_ml[(prow + r) * 2 + 1] = lsum;
   }
   const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
   __syncthreads(); // every wave is done with the last K/V tile
@@ -241,7 +241,7 @@ __global__ __launch_bounds__(NT * HPW * 64) void k_attn_mfma(const bf16_t *__res
   for (int i = 0; i < 4; ++i) {
     const int c = i * 64 + lane, rr = c >> 4, cc = c & 15;
     const u32x4 v = *reinterpret_cast<const u32x4 *>(blk + rr * 256 + ((cc ^ rr) << 4));
-    if (wt * 16 + rr < n) pa[(row0 + rr) * 16 + cc] = v; // plain store: the merge pass finds these in L2
+    if (wt * 16 + rr < n) pa[(prow + rr) * 16 + cc] = v; // plain store: the merge pass finds these in L2
   }
 }
 
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(ATT1_WAVES * 64) void k_attn_tile(const bf16_t *__r
                                                              int32_t cap, int32_t n, int32_t NT,
                                                              const uint64_t *__restrict__ anc,
                                                              const int32_t *__restrict__ d_len, bf16_t *__restrict__ out,
-                                                             int32_t out_row_tiles) {
+                                                             int32_t out_row_tiles, int32_t row0) {
   extern __shared__ f32x4 att1_lds[]; // ATT1_LDS_BYTES
   f32x4 (*s_acc)[8][64] = reinterpret_cast<f32x4 (*)[8][64]>(att1_lds);                         // [waves][8][64], 64 KiB
   float (*s_ml)[16][2] = reinterpret_cast<float (*)[16][2]>(att1_lds + ATT1_WAVES * 8 * 64);    // [waves][16][2]
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(ATT1_WAVES * 64) void k_attn_tile(const bf16_t *__r
     for (int c = 0; c < 8; ++c) vq[buf][c] = __builtin_nontemporal_load(Vh + (size_t)tile * 512 + c * 64);
   };
   if ((wave + 1) * 32 <= cap) fetch(0, wave); // inside the allocation even if beyond the sequence
-  const int L = *d_len;
+  const int L = *d_len + row0;
   const int total = L + n;
   const int n_tiles = (total + 31) >> 5;
   int i = 0;
@@ -393,7 +393,7 @@ __global__ __launch_bounds__(ATT1_WAVES * 64) void k_attn_tile(const bf16_t *__r
   ushort4 o;
   o.x = f32_to_bf16(num[0] * inv); o.y = f32_to_bf16(num[1] * inv);
   o.z = f32_to_bf16(num[2] * inv); o.w = f32_to_bf16(num[3] * inv);
-  const size_t idx = out_row_tiles > 0 ? act_frag_index(node, h * 128 + d, out_row_tiles) : ((size_t)node * H + h) * 128 + d;
+  const size_t idx = out_row_tiles > 0 ? act_frag_index(node + row0, h * 128 + d, out_row_tiles) : ((size_t)node * H + h) * 128 + d;
   store_stream(out + idx, o);
 }
 
@@ -402,7 +402,7 @@ __global__ __launch_bounds__(ATT1_WAVES * 64) void k_attn_tile(const bf16_t *__r
 // 4 features per node; all loads of a thread are issued before any arithmetic.
 __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ part_ml, const float *__restrict__ part_acc,
                                                     int32_t H, int32_t n, int32_t nsplit, bf16_t *__restrict__ out,
-                                                    int32_t out_row_tiles) {
+                                                    int32_t out_row_tiles, int32_t row0) {
   const int node = blockIdx.x * 8 + (threadIdx.x >> 5), h = blockIdx.y, d = (threadIdx.x & 31) * 4;
   if (node >= n) return;
   float2 ml[ATTN_MAX_SPLITS];
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
   ushort4 o;
   o.x = f32_to_bf16(num.x * inv); o.y = f32_to_bf16(num.y * inv);
   o.z = f32_to_bf16(num.z * inv); o.w = f32_to_bf16(num.w * inv);
-  const size_t idx = out_row_tiles > 0 ? act_frag_index(node, h * 128 + d, out_row_tiles)
+  const size_t idx = out_row_tiles > 0 ? act_frag_index(node + row0, h * 128 + d, out_row_tiles)
                                        : ((size_t)node * H + h) * 128 + d;
   store_stream(out + idx, o);
 }
@@ -457,22 +457,22 @@ int attn_choose_splits(int32_t head_groups, int32_t len_bound) {
 template <int NT, int HPW>
 static hipError_t launch_attn_k(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                                 int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t nsplit, float *part_ml,
-                                float *part_acc, bf16_t *out, int32_t out_row_tiles, KernelTimer tm, hipStream_t st) {
+                                float *part_acc, bf16_t *out, int32_t out_row_tiles, int32_t row0, KernelTimer tm, hipStream_t st) {
   return launch(k_attn_mfma<NT, HPW>, dim3(Hkv, H / Hkv / HPW, nsplit), dim3(NT * HPW * 64), 0, st, tm, q, Kl, Vl, H, Hkv,
-                cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles);
+                cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0);
 }
 
 template <int NT>
 static hipError_t launch_attn_nt(int hpw, const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv,
                                  int32_t cap, int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t nsplit,
-                                 float *part_ml, float *part_acc, bf16_t *out, int32_t out_row_tiles, KernelTimer tm,
+                                 float *part_ml, float *part_acc, bf16_t *out, int32_t out_row_tiles, int32_t row0, KernelTimer tm,
                                  hipStream_t st) {
   if constexpr (NT <= 6) {
     if (hpw == 2)
-      return launch_attn_k<NT, 2>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st);
+      return launch_attn_k<NT, 2>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0, tm, st);
   }
   if (hpw != 1) return hipErrorInvalidValue;
-  return launch_attn_k<NT, 1>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st);
+  return launch_attn_k<NT, 1>(q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0, tm, st);
 }
 
 // The one-launch form pays when a compute unit can pull its head's whole sequence in less time than the
@@ -485,7 +485,7 @@ bool attn_one_launch(int32_t H, int32_t Hkv, int32_t len_bound) { return len_bou
 
 hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                             int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t len_bound, float *part_ml,
-                            float *part_acc, bf16_t *out, int32_t out_row_tiles, Profiler *prof, hipStream_t st) {
+                            float *part_acc, bf16_t *out, int32_t out_row_tiles, int32_t row0, Profiler *prof, hipStream_t st) {
   if (Hkv < 1 || H % Hkv != 0) return hipErrorInvalidValue;
   const KernelTimer tm = prof_next(prof, PC_ATTN);
   if (attn_one_launch(H, Hkv, len_bound)) {
@@ -494,24 +494,24 @@ hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)ATT1_LDS_BYTES) == hipSuccess;
     if (!once) return hipErrorInvalidValue;
     return launch(k_attn_tile<0>, dim3(((H + 7) / 8) * 8 * NT), dim3(ATT1_WAVES * 64), ATT1_LDS_BYTES, st, tm, q, Kl, Vl,
-                  H, Hkv, cap, n, NT, anc, d_len, out, out_row_tiles);
+                  H, Hkv, cap, n, NT, anc, d_len, out, out_row_tiles, row0);
   }
   const int hpw = attn_heads_per_wg(H, Hkv, n);
   const int nsplit = attn_choose_splits(H / hpw, len_bound);
   hipError_t e = hipErrorInvalidValue;
   switch ((n + 15) / 16) {
-  case 1: e = launch_attn_nt<1>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
-  case 2: e = launch_attn_nt<2>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
-  case 3: e = launch_attn_nt<3>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
-  case 4: e = launch_attn_nt<4>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
-  case 5: e = launch_attn_nt<5>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
-  case 6: e = launch_attn_nt<6>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
-  case 7: e = launch_attn_nt<7>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
-  case 8: e = launch_attn_nt<8>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, tm, st); break;
+  case 1: e = launch_attn_nt<1>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0, tm, st); break;
+  case 2: e = launch_attn_nt<2>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0, tm, st); break;
+  case 3: e = launch_attn_nt<3>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0, tm, st); break;
+  case 4: e = launch_attn_nt<4>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0, tm, st); break;
+  case 5: e = launch_attn_nt<5>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0, tm, st); break;
+  case 6: e = launch_attn_nt<6>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0, tm, st); break;
+  case 7: e = launch_attn_nt<7>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0, tm, st); break;
+  case 8: e = launch_attn_nt<8>(hpw, q, Kl, Vl, H, Hkv, cap, n, anc, d_len, nsplit, part_ml, part_acc, out, out_row_tiles, row0, tm, st); break;
   }
   if (e != hipSuccess || nsplit == 1) return e;
   return launch(k_attn_merge, dim3((n + 7) / 8, H), dim3(256), 0, st, prof_next(prof, PC_ATTN_MERGE), part_ml, part_acc, H,
-                n, nsplit, out, out_row_tiles);
+                n, nsplit, out, out_row_tiles, row0);
 }
 
 } // namespace tr

@@ -22,21 +22,23 @@ Workspace plan_workspace(const tr_model &m) {
   const bool generic = !packed_supported(m); // the packed path keeps neither raw Q/K/V nor gate/up outputs
   const size_t esz = dtype_size(m.dtype);
   const size_t hq = (size_t)m.n_heads * m.head_dim, hk = (size_t)m.n_kv_heads * m.head_dim;
+  const size_t R = generic ? NP : NPW; // rows of the activation buffers
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
-  w.x = take((size_t)NP * m.d_model * 4);
-  w.xn = take((size_t)NP * m.d_model * esz);
+  w.x = take(R * m.d_model * 4);
+  w.xn = take(R * m.d_model * esz);
   w.qkv = take(generic ? (size_t)NP * (hq + 2 * hk) * 4 : 0);
-  w.q = take((size_t)NP * hq * esz);
-  w.attn = take((size_t)NP * hq * esz);
+  w.q = take(R * hq * esz);
+  w.attn = take(R * hq * esz);
   w.gu = take(generic ? (size_t)NP * 2 * m.d_ffn * 4 : 0);
-  w.h = take((size_t)NP * m.d_ffn * esz);
-  w.rope = take((size_t)NP * m.head_dim * 4);
+  w.h = take(R * m.d_ffn * esz);
+  w.rope = take(R * m.head_dim * 4);
   w.logits = take((size_t)NP * m.vocab * 4);
   w.part_ml = take((size_t)ATTN_MAX_SPLITS * NP * m.n_heads * 2 * 4);
   w.part_acc = take((size_t)ATTN_MAX_SPLITS * NP * m.n_heads * m.head_dim * 4);
-  w.ypart = take((size_t)GEMM_MAX_SPLITS * NP * m.d_model * 4);
-  w.ssq = take((size_t)NP * ((m.d_model + 1023) / 1024) * 4);
+  w.ypart = take((generic ? (size_t)GEMM_MAX_SPLITS * NP : (size_t)WIDE_MAX_SPLITS * NPW) * m.d_model * 4);
+  static_assert(WIDE_MAX_SPLITS * NPW >= GEMM_MAX_SPLITS * NP, "ypart serves both paths");
+  w.ssq = take(R * ((m.d_model + 1023) / 1024) * 4);
   w.total = off;
   return w;
 }
@@ -44,6 +46,7 @@ Workspace plan_workspace(const tr_model &m) {
 // ---------------------------------------------------------------------------------------------
 // Embedding gather + rotary table.  Row n: x[n,:] = E[tok[n],:]; cos/sin of (L + depth[n]) * f_i
 // with f_i = theta^(-2i/hd), evaluated in double so that long positions keep float32 accuracy.
+// depth == nullptr: row n sits n positions after L (a run of consecutive prompt tokens).
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_embed_rope(const T *__restrict__ E, int32_t V, int32_t d,
@@ -56,7 +59,7 @@ __global__ __launch_bounds__(256) void k_embed_rope(const T *__restrict__ E, int
   const T *src = E + (size_t)t * d;
   for (int j = threadIdx.x; j < d; j += blockDim.x) x[(size_t)n * d + j] = to_f32<T>(src[j]);
   const int half = hd / 2;
-  const double pos = (double)(*d_len + depth[n]);
+  const double pos = (double)(*d_len + (depth != nullptr ? depth[n] : n));
   for (int i = threadIdx.x; i < half; i += blockDim.x) {
     const double f = pow((double)theta, -2.0 * (double)i / (double)hd);
     double sn, cs;
@@ -302,7 +305,7 @@ static hipError_t attention_dispatch(const tr_kv &kv, int32_t layer, int32_t H, 
   if (kv.layout == TR_KV_TILED) {
     return launch_attn_mfma((const bf16_t *)q, (const bf16_t *)Kl, (const bf16_t *)Vl, H, kv.n_kv_heads, kv.capacity,
                             n, tree.anc, kv.d_len, kv.len_bound + n, part_ml, part_acc, (bf16_t *)out, out_row_tiles,
-                            prof, st);
+                            0, prof, st);
   }
   return launch(k_attn_generic<T>, dim3(n, H), dim3(256), 0, st, prof_next(prof, PC_ATTN), q, Kl, Vl, H, kv.n_kv_heads,
                 kv.head_dim, kv.capacity, n, tree.anc, kv.d_len, out, out_row_tiles);
@@ -528,6 +531,103 @@ static hipError_t forward_packed(const tr_model &m, const tr_kv &kv, const TreeD
   return hipSuccess;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Prompt ingestion on the packed path: up to NPW rows per pass.  The projections take all rows at once
+// (tr_gemm_wide.hip: the layer's weights are read from memory once per pass instead of once per 128 rows);
+// attention runs per block of 128 rows with the chain masks, each block seeing the committed length plus the
+// rows before it as its prefix (their keys and values are in the cache by then: the Q/K/V projection of the
+// whole pass precedes it).  Same arithmetic per row as forward_packed with one K-split.
+// ---------------------------------------------------------------------------------------------
+static hipError_t forward_wide(const tr_model &m, const tr_kv &kv, const TreeDev &chain, int32_t n, const int32_t *tok,
+                               unsigned char *ws, hipStream_t st) {
+  typedef bf16_t T;
+  const Workspace w = plan_workspace(m);
+  const int d = m.d_model, H = m.n_heads, Hkv = m.n_kv_heads, hd = m.head_dim, F = m.d_ffn;
+  const int hq = H * hd, hk = Hkv * hd;
+  const int RT = (n + 15) / 16;
+  float *x = (float *)(ws + w.x);
+  T *xn = (T *)(ws + w.xn);
+  T *q = (T *)(ws + w.q);
+  T *attn = (T *)(ws + w.attn);
+  T *hbuf = (T *)(ws + w.h);
+  float *rope = (float *)(ws + w.rope);
+  float *ypart = (float *)(ws + w.ypart);
+  const size_t lsz = (size_t)Hkv * kv.capacity * hd;
+  float *ssq = (float *)(ws + w.ssq);
+  const int nch = (d + NORM_CHUNK - 1) / NORM_CHUNK;
+  const KernelTimer no_timer{};
+  const size_t ystride = (size_t)NPW * d;
+
+  TR_TRY(launch(k_embed_rope<T>, dim3(n), dim3(256), 0, st, no_timer, (const T *)m.embed, m.vocab, d, tok,
+                (const int32_t *)nullptr, kv.d_len, hd, m.rope_theta, x, rope));
+  int pending = 0;
+  auto add_norm = [&](const void *gain) {
+    return launch(k_add_frag, dim3(RT * 16, nch), dim3(128), 0, st, no_timer, x, ypart, pending, ystride,
+                  (const T *)gain, n, d, RT, xn, ssq, nch);
+  };
+  for (int l = 0; l < m.n_layers; ++l) {
+    const tr_layer &lw = m.layers[l];
+    TR_TRY(add_norm(lw.attn_norm));
+    {
+      GemmArgs g{};
+      g.a_frag = xn; g.n = n; g.K = d;
+      g.seg[0] = GemmSeg{(const T *)lw.wq, hq / 16};
+      g.seg[1] = GemmSeg{(const T *)lw.wk, hk / 16};
+      g.seg[2] = GemmSeg{(const T *)lw.wv, hk / 16};
+      g.n_seg = 3; g.mode = GEMM_STORE;
+      g.row_ssq = ssq; g.n_ssq = nch; g.norm_dim = d; g.eps = m.rms_eps;
+      g.rope = GemmRope{q, (T *)kv.k + (size_t)l * lsz, (T *)kv.v + (size_t)l * lsz, rope, kv.d_len,
+                        H, Hkv, hd, kv.capacity, kv.layout};
+      TR_TRY(launch_gemm_wide(g, 1, nullptr, st));
+    }
+    if (l == m.n_layers - 1) break; // ingestion only needs the cache: nothing reads the last layer's output
+    for (int r0 = 0; r0 < n; r0 += NP) {
+      const int nb = n - r0 < NP ? n - r0 : NP;
+      TR_TRY(launch_attn_mfma(q + (size_t)r0 * hq, (const T *)kv.k + (size_t)l * lsz, (const T *)kv.v + (size_t)l * lsz, H,
+                              Hkv, kv.capacity, nb, chain.anc, kv.d_len, kv.len_bound + r0 + nb,
+                              (float *)(ws + w.part_ml), (float *)(ws + w.part_acc), attn, RT, r0, nullptr, st));
+    }
+    {
+      GemmArgs g{};
+      g.a_frag = attn; g.n = n; g.K = hq;
+      g.seg[0] = GemmSeg{(const T *)lw.wo, d / 16};
+      g.n_seg = 1; g.y = ypart; g.ldy = d; g.split_stride = ystride; g.mode = GEMM_STORE;
+      TR_TRY(launch_gemm_wide(g, WIDE_MAX_SPLITS, &pending, st));
+    }
+    TR_TRY(add_norm(lw.ffn_norm));
+    {
+      GemmArgs g{};
+      g.a_frag = xn; g.n = n; g.K = d;
+      g.seg[0] = GemmSeg{(const T *)lw.w_gate, F / 16};
+      g.n_seg = 1; g.w2 = (const T *)lw.w_up; g.h_frag = hbuf; g.mode = GEMM_SWIGLU;
+      g.row_ssq = ssq; g.n_ssq = nch; g.norm_dim = d; g.eps = m.rms_eps;
+      TR_TRY(launch_gemm_wide(g, 1, nullptr, st));
+    }
+    {
+      GemmArgs g{};
+      g.a_frag = hbuf; g.n = n; g.K = F;
+      g.seg[0] = GemmSeg{(const T *)lw.w_down, d / 16};
+      g.n_seg = 1; g.y = ypart; g.ldy = d; g.split_stride = ystride; g.mode = GEMM_STORE;
+      TR_TRY(launch_gemm_wide(g, WIDE_MAX_SPLITS, &pending, st));
+    }
+  }
+  return hipSuccess;
+}
+
+static bool wide_supported(const tr_model &m, const tr_kv &kv) {
+  return packed_supported(m) && kv.layout == TR_KV_TILED && kv.dtype == TR_BF16 && m.head_dim == 128 &&
+         m.d_model >= 64 && m.d_ffn >= 64;
+}
+
+int32_t prefill_rows(const tr_model &m, const tr_kv &kv) { return wide_supported(m, kv) ? NPW : NP; }
+
+hipError_t run_prefill_pass(const tr_model &m, const tr_kv &kv, const TreeDev &chain, int32_t n, const int32_t *d_tokens,
+                            void *ws, hipStream_t st) {
+  if (n > NP && wide_supported(m, kv) && n <= NPW) return forward_wide(m, kv, chain, n, d_tokens, (unsigned char *)ws, st);
+  if (n > NP) return hipErrorInvalidValue;
+  return run_forward(m, kv, chain, n, d_tokens, nullptr, ws, nullptr, st);
+}
+
 hipError_t run_forward(const tr_model &m, const tr_kv &kv, const TreeDev &tree, int32_t n, const int32_t *d_tokens,
                        float *write_logits, void *ws, Profiler *prof, hipStream_t st) {
   if (packed_supported(m)) return forward_packed(m, kv, tree, n, d_tokens, write_logits, (unsigned char *)ws, prof, st);
@@ -567,10 +667,14 @@ hipError_t run_linear(const void *x, const void *w, int32_t dtype, int32_t layou
     g.seg[0] = GemmSeg{(const bf16_t *)w, out_f / 16};
     g.n_seg = 1; g.y = splits > 1 ? part : y; g.ldy = out_f;
     g.split_stride = (size_t)n * out_f; g.mode = GEMM_STORE;
-    gemm_plan(g, splits);
-    g.splits = splits; // the caller's split count is used as given
-    TR_TRY(launch_gemm_mfma(g, st));
-    if (splits > 1) {
+    if (n > NP) { // the prompt-ingestion kernel; it may use fewer splits than allowed
+      TR_TRY(launch_gemm_wide(g, splits, &splits, st));
+    } else {
+      gemm_plan(g, splits);
+      g.splits = splits; // the caller's split count is used as given
+      TR_TRY(launch_gemm_mfma(g, st));
+    }
+    if (g.y != y) {
       const size_t count = (size_t)n * out_f;
       TR_TRY(launch(k_sum_parts, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, KernelTimer{}, part, splits,
                     (size_t)n * out_f, count, y));

@@ -63,7 +63,9 @@ struct TreeDev {
   const uint64_t *anc;   // [n][2]
 };
 
-// Workspace carve-up (byte offsets, all 256-aligned).  Buffers are sized for TR_MAX_NODES rows.
+// Workspace carve-up (byte offsets, all 256-aligned).  Buffers are sized for NP = TR_MAX_NODES rows; for models
+// the packed path serves, the activation buffers (x, xn, q, attn, h, rope, ssq, and ypart as one complete sum)
+// hold NPW rows, which is what one prompt-ingestion pass takes.
 struct Workspace {
   size_t x;        // float  [NP, d]            residual stream
   size_t xn;       // T      [NP, d]            normalised activations
@@ -81,6 +83,7 @@ struct Workspace {
   size_t total;
 };
 constexpr int NP = TR_MAX_NODES;
+constexpr int NPW = TR_PREFILL_ROWS;
 constexpr int ATTN_MAX_SPLITS = 16;
 constexpr int GEMM_MAX_SPLITS = 4;
 
@@ -167,6 +170,12 @@ hipError_t launch_stream(const void *src, void *dst, size_t bytes, hipStream_t s
 // Runs rows `tokens` through the model.  `write_logits` may be NULL (no LM head).
 hipError_t run_forward(const tr_model &m, const tr_kv &kv, const TreeDev &tree, int32_t n,
                        const int32_t *d_tokens, float *write_logits, void *ws, Profiler *prof, hipStream_t s);
+// Prompt ingestion: rows one pass may take for this model and cache (NPW on the packed path with a tiled cache,
+// else NP), and the pass itself: n consecutive prompt tokens, causal, keys / values appended at the committed
+// length (which the caller advances afterwards), no logits.
+int32_t prefill_rows(const tr_model &m, const tr_kv &kv);
+hipError_t run_prefill_pass(const tr_model &m, const tr_kv &kv, const TreeDev &chain, int32_t n,
+                            const int32_t *d_tokens, void *ws, hipStream_t s);
 hipError_t run_tree_attention(const tr_kv &kv, int32_t layer, int32_t H, const TreeDev &tree,
                               const void *d_q, void *d_out, void *ws, hipStream_t s);
 size_t linear_workspace_bytes(int32_t n, int32_t in_f, int32_t out_f, int32_t splits);

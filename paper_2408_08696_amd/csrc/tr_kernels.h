@@ -84,6 +84,14 @@ bool gemm_mfma_supported(int32_t n, int32_t K, int32_t O);
 hipError_t launch_gemm_mfma(const GemmArgs &g, hipStream_t st, KernelTimer tm = KernelTimer{});
 // rope_hd > 0: packed row h*rope_hd + 2j + b takes source row h*rope_hd + j + b*rope_hd/2 (query / key
 // matrices: the two features of a rotation pair become neighbours)
+// Prompt ingestion: the same contraction and epilogues for up to WIDE_MAX_ROWS rows per launch (tr_gemm_wide.hip);
+// a_frag / h_frag span ceil(n / 16) row tiles, rope rows are indexed by row; a plain store may be split over k
+// into up to max_splits partial sums split_stride floats apart (*out_splits receives the count used).
+constexpr int WIDE_MAX_ROWS = NPW;
+constexpr int WIDE_MAX_SPLITS = 4;
+bool gemm_wide_supported(int32_t n, int32_t K, int32_t O);
+hipError_t launch_gemm_wide(const GemmArgs &g, int32_t max_splits, int32_t *out_splits, hipStream_t st,
+                            KernelTimer tm = KernelTimer{});
 hipError_t launch_pack_weight(const bf16_t *src, bf16_t *dst, int32_t O, int32_t K, int32_t rope_hd, hipStream_t st);
 
 // Tree attention for head_dim 128, bf16 K/V/Q, split over the key axis with a merge pass.
@@ -94,8 +102,11 @@ int attn_heads_per_wg(int32_t H, int32_t Hkv, int32_t n);
 int attn_choose_splits(int32_t head_groups, int32_t len_bound);
 // true: one launch without key splits or merge pass (short sequences); then the two values above do not apply
 bool attn_one_launch(int32_t H, int32_t Hkv, int32_t len_bound);
+// row0 (prompt ingestion in blocks of rows): the rows are rows row0 .. row0 + n - 1 of a longer pass whose
+// keys and values are already cached; they see the committed length plus row0 positions as prefix, node j of
+// this launch sits at that prefix length + j, and with out_row_tiles > 0 the output lands at row row0 + j.
 hipError_t launch_attn_mfma(const bf16_t *q, const bf16_t *Kl, const bf16_t *Vl, int32_t H, int32_t Hkv, int32_t cap,
                             int32_t n, const uint64_t *anc, const int32_t *d_len, int32_t len_bound, float *part_ml,
-                            float *part_acc, bf16_t *out, int32_t out_row_tiles, Profiler *prof, hipStream_t st);
+                            float *part_acc, bf16_t *out, int32_t out_row_tiles, int32_t row0, Profiler *prof, hipStream_t st);
 
 } // namespace tr

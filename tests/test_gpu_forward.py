@@ -188,32 +188,42 @@ def test_prefill_crosses_chunk_boundaries():
         assert np.abs(vg[l] - kv.v[l][:299]).max() < 1e-4
 
 
-@pytest.mark.parametrize("shape_name", ["tiny_bf16", "tiny_gqa_bf16"])
-def test_packed_prefill_cache_matches_oracle(shape_name):
+@pytest.mark.parametrize("shape_name,plen", [("tiny_bf16", 100), ("tiny_bf16", 150), ("tiny_gqa_bf16", 150),
+                                             ("tiny_bf16", 513), ("tiny_gqa_bf16", 600), ("tiny_bf16", 700),
+                                             ("zoo_heads32", 300), ("tiny_gqa_bf16", 1100)])
+def test_packed_prefill_cache_matches_oracle(shape_name, plen):
     """Packed bf16 models rotate and store queries, keys and values in the epilogue of the fused Q/K/V
     projection; the committed cache must hold the oracle's keys (read back through the interleaved feature
-    order of such models) and values, to bf16 accuracy."""
+    order of such models) and values, to bf16 accuracy.  With a tiled cache, prompts beyond 128 tokens go
+    through the wide projection kernel in passes of up to 512 rows with attention per block of 128: the
+    lengths cover one decode-path pass (99 rows), a ragged second block (149), exactly one full pass (512), a
+    full pass plus a decode-path remainder (599 = 512 + 87), plus a ragged wide pass (699 = 512 + 187), a
+    single-layer model (only the Q/K/V projection runs) and two full passes (1099 = 512 + 512 + 75)."""
     require_gpu()
-    say("packed prefill cache", shape_name)
+    say("packed prefill cache", shape_name, plen)
     sh = synth.SHAPES[shape_name]
     w = synth.make_weights(sh, seed=2)
     wn = synth.weights_to_numpy(w)
-    prompt = synth.zipf_prompt(sh.vocab, 150, seed=2).tolist()
-    eng = tr.Engine(sh, to_gpu(w), synth.tree15(), k=K, capacity=256)
-    assert eng.model.packed
+    prompt = synth.zipf_prompt(sh.vocab, plen, seed=2).tolist()
+    eng = tr.Engine(sh, to_gpu(w), synth.tree15(), k=K, capacity=plen + 106)
+    assert eng.model.packed and eng.kv.tiled
     eng.prefill(prompt)
     torch.cuda.synchronize()
+    n = plen - 1
+    assert int(eng.kv.d_len.item()) == n and eng.kv.c.len_bound == n
     cfg = oracle_cfg(sh)
-    kv = O.KVCache(cfg, 256)
+    kv = O.KVCache(cfg, plen + 106)
     O.prefill(cfg, wn, kv, prompt[:-1])
     kp, vp = kv_plain_views(eng.kv, k_interleaved=True)
-    kg = kp[:, :, :149, :].permute(0, 2, 1, 3).float().cpu().numpy()
-    vg = vp[:, :, :149, :].permute(0, 2, 1, 3).float().cpu().numpy()
+    kg = kp[:, :, :n, :].permute(0, 2, 1, 3).float().cpu().numpy()
+    vg = vp[:, :, :n, :].permute(0, 2, 1, 3).float().cpu().numpy()
     for l in range(sh.n_layers):
-        ek = np.abs(kg[l] - kv.k[l][:149]).max() / np.abs(kv.k[l][:149]).max()
-        ev = np.abs(vg[l] - kv.v[l][:149]).max() / np.abs(kv.v[l][:149]).max()
-        say("layer", l, "relative K error", ek, "V error", ev)
-        assert ek < 2e-2 and ev < 2e-2
+        # per row, so that a wrong row in one block cannot hide behind the largest entry of the whole cache
+        dk = np.abs(kg[l] - kv.k[l][:n]).max(axis=(1, 2)) / np.abs(kv.k[l][:n]).max(axis=(1, 2))
+        dv = np.abs(vg[l] - kv.v[l][:n]).max(axis=(1, 2)) / np.abs(kv.v[l][:n]).max(axis=(1, 2))
+        say("layer", l, "relative K error", dk.max(), "at row", int(dk.argmax()), "V error", dv.max(), "at row",
+            int(dv.argmax()))
+        assert dk.max() < 2e-2 and dv.max() < 2e-2
 
 
 def test_pack_weight_rope_interleaves_rows():
@@ -297,10 +307,18 @@ def test_tree_attention_matches_per_path_attention(tmpl_name, H, Hkv, L, tiled):
 
 @pytest.mark.parametrize("n,K_,O_,splits", [(80, 4096, 4096, 2), (80, 11008, 4096, 2), (81, 4096, 1024, 4),
                                             (1, 4096, 512, 1), (128, 512, 2048, 1), (16, 256, 64, 1),
-                                            (80, 1024, 32000, 1), (80, 4096, 12288, 1), (37, 96, 32, 3)])
+                                            (80, 1024, 32000, 1), (80, 4096, 12288, 1), (37, 96, 32, 3),
+                                            # above 128 rows: the prompt-ingestion kernel in each of its shapes
+                                            (129, 64, 32, 1), (250, 4096, 4096, 4), (256, 736, 2080, 1),
+                                            (300, 256, 18432, 1), (511, 4096, 4608, 4), (512, 11008, 4096, 4),
+                                            (401, 4096, 1024, 4), (300, 2240, 96, 3)])
 def test_linear_bf16_packed_matches_oracle_matmul(n, K_, O_, splits):
     """The projection kernel alone (packed weights, MFMA) against a float64 matrix product of the
-    same bf16 values; also checks the repack kernel, since a misplaced element would show here."""
+    same bf16 values; also checks the repack kernel, since a misplaced element would show here.
+    Row counts above 128 reach the prompt-ingestion kernel: 12 out-tiles x 2 row tiles per wave up to 256 rows
+    (ragged tile groups at 2080 features, an odd number of k-steps at 736), 6 x 4 with one workgroup over all
+    rows when the out-features or the k-splits fill the chip (18432 features; 4608 features x 4 splits), else
+    6 x 2 (k-split shares rounded to whole stages: 344 k-steps as 116 + 116 + 112, 70 as 36 + 34)."""
     require_gpu()
     say("linear packed", n, K_, O_, splits)
     x = synth.normal_tensor((n, K_), 1.0, seed=n + K_, dtype=torch.bfloat16)
