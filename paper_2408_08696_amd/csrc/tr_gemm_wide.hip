@@ -42,7 +42,6 @@ constexpr int WIDE_WAVES = 8;
 constexpr int WIDE_TPS = 24;                    // weight tiles per LDS stage (24 KiB)
 constexpr int WIDE_TPW = WIDE_TPS / WIDE_WAVES; // tiles a wave loads per stage
 constexpr int WIDE_PA = 4;                      // k-steps of activation tiles a wave keeps in flight
-constexpr int WIDE_TARGET_WGS = 256;            // workgroups a launch should have at least
 
 // NW: out-tiles per workgroup (SwiGLU: NW / 2 gate + NW / 2 up); RTW: row tiles per wave.
 template <int MODE, bool SCALED, int NW, int RTW>
@@ -294,8 +293,7 @@ static hipError_t launch_shape(const GemmArgs &g, int row_tiles, unsigned grid, 
 // (<= WIDE_MAX_ROWS); a_frag / h_frag use ceil(n / 16) row tiles; the RMS scale takes at most 8 partial sums per
 // row.  max_splits > 1 (plain store without scale only): y[s] = y + s * split_stride receives the partial sum
 // of k-range s, and *out_splits how many the launch used.
-//   rows <= 256: 12 out-tiles x 2 row tiles per wave;  above: 6 x 4 (one workgroup spans all rows), unless that
-//   leaves the chip underfilled even with k-splits, then 6 x 2 with two row blocks.
+//   Shapes: 12 out-tiles x 2 row tiles per wave, 6 x 4 (one workgroup spans 512 rows) or 6 x 2.
 hipError_t launch_gemm_wide(const GemmArgs &args, int32_t max_splits, int32_t *out_splits, hipStream_t st, KernelTimer tm) {
   GemmArgs g = args;
   if (g.n < 1 || g.n > WIDE_MAX_ROWS || g.K % 32 != 0 || g.K < 64 || (g.row_ssq != nullptr && g.n_ssq > 8))
@@ -307,27 +305,34 @@ hipError_t launch_gemm_wide(const GemmArgs &args, int32_t max_splits, int32_t *o
   const int row_tiles = (g.n + 15) / 16;
   const int unit = g.mode == GEMM_SWIGLU ? 2 : 1; // a gate/up pair occupies two of the NW tiles
   auto groups_of = [&](int nw) { return (total + nw / unit - 1) / (nw / unit); };
-  auto splits_for = [&](int wgs, int ks) {
-    if (!may_split) return 1;
-    int s = (WIDE_TARGET_WGS + wgs - 1) / wgs;
-    const int by_depth = g.K / 32 / (8 * ks); // at least 8 stages per split
-    if (s > by_depth) s = by_depth;
-    if (s > max_splits) s = max_splits;
-    if (s < 1) s = 1;
-    while (s > 1) { // the rounded-up share of the last split must not be empty
-      int per_k = (g.K / 32 + s - 1) / s;
+  // Shape and K-splits by a cost model of what bounds the kernel, the KiB a workgroup pulls per k-step (its row
+  // tiles and its weight tiles, 1 KiB each) times its k-steps, per round of 256 workgroups, plus a fixed cost
+  // per round (ramp and epilogue, in the same unit) and what the partial sums of a K-split cost to write and
+  // re-read.
+  const int KT = g.K / 32;
+  int nw = 12, rtw = 2, best_splits = 1;
+  double best = 1e30;
+  static const int cand[3][2] = {{12, 2}, {6, 4}, {6, 2}};
+  for (int c = 0; c < 3; ++c) {
+    const int cnw = cand[c][0], crtw = cand[c][1], ks = WIDE_TPS / cnw;
+    if (row_tiles <= 16 && crtw == 4) continue;
+    const int rb = (row_tiles + WIDE_WAVES * crtw - 1) / (WIDE_WAVES * crtw);
+    const int rows_wg = row_tiles < WIDE_WAVES * crtw ? row_tiles : WIDE_WAVES * crtw;
+    for (int sp = 1; sp <= (may_split ? max_splits : 1); ++sp) {
+      int per_k = (KT + sp - 1) / sp;
       per_k = (per_k + ks - 1) / ks * ks;
-      if ((s - 1) * per_k < g.K / 32) break;
-      --s;
+      if (sp > 1 && (per_k < 8 * ks || (sp - 1) * per_k >= KT)) continue; // at least 8 stages, no empty share
+      const int wgs = groups_of(cnw) * rb * sp;
+      const int rounds = (wgs + 255) / 256;
+      double cost = rounds * ((double)per_k * (rows_wg + cnw) + 150.0);
+      if (sp > 1) cost += sp * 160.0 * row_tiles / 32.0;
+      if (cost < best) {
+        best = cost;
+        nw = cnw;
+        rtw = crtw;
+        best_splits = sp;
+      }
     }
-    return s;
-  };
-  int nw, rtw;
-  if (row_tiles <= 16) { nw = 12; rtw = 2; }
-  else {
-    nw = 6; rtw = 4;
-    const int wgs4 = groups_of(6) * splits_for(groups_of(6), 4);
-    if (wgs4 < WIDE_TARGET_WGS * 3 / 4) rtw = 2;
   }
   const int row_blocks = (row_tiles + WIDE_WAVES * rtw - 1) / (WIDE_WAVES * rtw);
   g.total_tiles = total;
@@ -335,7 +340,7 @@ hipError_t launch_gemm_wide(const GemmArgs &args, int32_t max_splits, int32_t *o
   g.groups = groups_of(nw);
   g.part_q = total / g.groups;
   g.part_rem = total % g.groups;
-  g.splits = splits_for(g.groups * row_blocks, WIDE_TPS / nw);
+  g.splits = best_splits;
   if (out_splits != nullptr) *out_splits = g.splits;
   const unsigned grid = (unsigned)(((g.groups + 7) / 8) * 8 * row_blocks * g.splits);
   if (nw == 12) return launch_shape<12, 2>(g, row_tiles, grid, st, tm);

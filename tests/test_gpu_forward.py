@@ -315,10 +315,11 @@ def test_tree_attention_matches_per_path_attention(tmpl_name, H, Hkv, L, tiled):
 def test_linear_bf16_packed_matches_oracle_matmul(n, K_, O_, splits):
     """The projection kernel alone (packed weights, MFMA) against a float64 matrix product of the
     same bf16 values; also checks the repack kernel, since a misplaced element would show here.
-    Row counts above 128 reach the prompt-ingestion kernel: 12 out-tiles x 2 row tiles per wave up to 256 rows
-    (ragged tile groups at 2080 features, an odd number of k-steps at 736), 6 x 4 with one workgroup over all
-    rows when the out-features or the k-splits fill the chip (18432 features; 4608 features x 4 splits), else
-    6 x 2 (k-split shares rounded to whole stages: 344 k-steps as 116 + 116 + 112, 70 as 36 + 34)."""
+    Row counts above 128 reach the prompt-ingestion kernel, whose launcher picks the workgroup shape (12 out-tiles
+    x 2 row tiles per wave, 6 x 4 with one workgroup over all rows, or 6 x 2) and the K-splits from a cost model:
+    the cases cover one and two row blocks, ragged out-tile groups (2080 features), an odd number of k-steps
+    (736), the 6 x 4 shape (18432 features), and K-split shares that are rounded to whole stages and leave a
+    shorter last share (11008, 2240 in-features)."""
     require_gpu()
     say("linear packed", n, K_, O_, splits)
     x = synth.normal_tensor((n, K_), 1.0, seed=n + K_, dtype=torch.bfloat16)
