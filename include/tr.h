@@ -292,10 +292,17 @@ tr_status tr_accept_and_update_sampled(tr_ctx *ctx, tr_kv *kv, const int32_t *d_
                                        tr_step_out *d_out, tr_step_out *h_out_or_null, void *stream);
 
 /*
- * Prompt ingestion through the same kernels: runs d_tokens [device] int32 [n_tokens] causally
- * after the committed prefix (a chain is a tree whose node i has ancestors 0..i), commits their
- * keys/values and advances *kv->d_len and kv->len_bound by n_tokens.  No logits, no matrix
- * update (the paper updates M only from decoding steps, Section 3.3).
+ * Prompt ingestion: runs d_tokens [device] int32 [n_tokens] causally after the committed prefix
+ * (a chain is a tree whose node i has ancestors 0..i), commits their keys/values and advances
+ * *kv->d_len and kv->len_bound by n_tokens.  No logits, no matrix update (the paper updates M only
+ * from decoding steps, Section 3.3).  Packed bf16 models with a tiled cache take TR_PREFILL_ROWS
+ * tokens per pass (a projection kernel of its own reads each layer's weights once per pass; the
+ * tree-attention kernels run per block of TR_MAX_NODES rows; the last layer stops after its K/V
+ * are cached); all other models, and what is left after the full passes when it is at most
+ * TR_MAX_NODES tokens, go through the decode-step kernels TR_MAX_NODES tokens at a time.  Same
+ * arithmetic per token either way.  Errors: TR_EINVAL (NULL, n_tokens < 0, model / cache
+ * mismatch), TR_ECAPACITY (kv->len_bound + n_tokens beyond the capacity, workspace smaller than
+ * tr_workspace_bytes), TR_EHIP.  n_tokens == 0 is a no-op.
  */
 tr_status tr_prefill(tr_ctx *ctx, const tr_model *model, tr_kv *kv, const int32_t *d_tokens,
                      int32_t n_tokens, void *d_workspace, size_t workspace_bytes, void *stream);
