@@ -16,11 +16,11 @@
 //
 // What bounds it (7B gate/up projection of 511 rows, 92 Gflop): with one row tile per wave the LDS set the pace
 // (every MFMA needs a 1 KiB tile read, the LDS delivers one per 8 clocks to the whole compute unit): 109 us.
-// With two or four row tiles per wave, 86-91 us, and the same whether the weights come from memory or from
-// cache, whether the LDS reads run one or two tile pairs ahead, and with either MFMA shape: what the shapes
-// have in common is the rate at which a compute unit receives global loads, 19-23 bytes per clock (activation
-// tiles are private to a wave, so the 230 workgroups together pull 1.2 GB through the L2s per launch).  At 512
-// rows the out-tile groups cannot grow without leaving compute units idle, so this is about 1.05 PFLOP/s.
+// With two or four row tiles per wave, 86-94 us = 1.0 PFLOP/s, and the same whether the weights come from memory
+// or from cache, whether the LDS reads run one or two tile pairs ahead or are left out, and with either MFMA
+// shape.  The matrix pipe is busy 45 % of that time and a compute unit receives 19-23 bytes per clock of global
+// loads, a third of what either can do alone: eight waves move in lockstep between the stage barriers, one
+// workgroup per compute unit, and nothing fills the time a wave spends in its waits.
 //
 // Same packed weight layout, fragment-ordered activations and epilogues (plain store, RoPE + cache append,
 // SwiGLU) as the decode kernel.
@@ -105,8 +105,8 @@ __global__ __launch_bounds__(WIDE_WAVES * 64) void k_gemm_wide(GemmArgs g, int32
     }
   };
 
-  // MFMA shape: v_mfma_f32_32x32x16_bf16, which runs at twice the rate of the 16x16x32 form on this chip
-  // (measured 2.3 against 1.2 PFLOP/s).  Its operands are rebuilt from the 16x32 fragment tiles by addressing
+  // MFMA shape: v_mfma_f32_32x32x16_bf16 (same rate per flop as the 16x16x32 form, half as many instructions and
+  // LDS reads per flop).  Its operands are rebuilt from the 16x32 fragment tiles by addressing
   // alone: for k-half h of a k-step, lane l supplies 8 k-values 16 h + 8 (l / 32) .. + 7 of item l % 32, i.e.
   // lane slot (l % 16) + 16 (2 h + l / 32) of the first (l % 32 < 16) or second tile of a pair.  A weight pair
   // is out-tiles (2p, 2p + 1), or for SwiGLU (gate tile p, up tile p); an activation pair is two consecutive row
