@@ -226,6 +226,35 @@ def test_packed_prefill_cache_matches_oracle(shape_name, plen):
         assert dk.max() < 2e-2 and dv.max() < 2e-2
 
 
+def test_packed_prefill_appends_after_a_committed_prefix():
+    """Two calls: 201 tokens, then 400 more on top (keep_cache).  The second call's wide pass starts at a
+    non-zero committed length, so its rotary positions, cache rows and attention prefixes are all offset;
+    the cache must equal the oracle's single causal prefill of all 600 tokens."""
+    require_gpu()
+    sh = synth.SHAPES["tiny_gqa_bf16"]
+    w = synth.make_weights(sh, seed=4)
+    wn = synth.weights_to_numpy(w)
+    prompt = synth.zipf_prompt(sh.vocab, 601, seed=4).tolist()
+    eng = tr.Engine(sh, to_gpu(w), synth.tree15(), k=K, capacity=720)
+    assert eng.model.packed and eng.kv.tiled
+    eng.prefill(prompt[:201])                      # commits 200, the 201st becomes the root and is dropped here
+    eng.prefill(prompt[200:], keep_cache=True)     # commits tokens 200 .. 599
+    torch.cuda.synchronize()
+    n = 600
+    assert int(eng.kv.d_len.item()) == n and eng.kv.c.len_bound == n
+    cfg = oracle_cfg(sh)
+    kv = O.KVCache(cfg, 720)
+    O.prefill(cfg, wn, kv, prompt[:n])
+    kp, vp = kv_plain_views(eng.kv, k_interleaved=True)
+    kg = kp[:, :, :n, :].permute(0, 2, 1, 3).float().cpu().numpy()
+    vg = vp[:, :, :n, :].permute(0, 2, 1, 3).float().cpu().numpy()
+    for l in range(sh.n_layers):
+        dk = np.abs(kg[l] - kv.k[l][:n]).max(axis=(1, 2)) / np.abs(kv.k[l][:n]).max(axis=(1, 2))
+        dv = np.abs(vg[l] - kv.v[l][:n]).max(axis=(1, 2)) / np.abs(kv.v[l][:n]).max(axis=(1, 2))
+        say("layer", l, "relative K error", dk.max(), "V error", dv.max())
+        assert dk.max() < 2e-2 and dv.max() < 2e-2
+
+
 def test_pack_weight_rope_interleaves_rows():
     """y = x W^T through a matrix packed with tr_pack_weight_rope comes out with output feature
     h*hd + 2j + b holding what feature h*hd + j + b*hd/2 holds with the plain packing."""
