@@ -86,8 +86,7 @@ __global__ __launch_bounds__(WIDE_WAVES * 64) void k_gemm_wide(GemmArgs g, int32
     wsrc[i] = reinterpret_cast<const u32x4 *>(mat) + (size_t)t * KT * 64 + lane;
   }
   const int n_stages = (k1 - k0 + KS - 1) / KS;
-  constexpr int D = 2; // weight stages in flight in registers
-  u32x4 wreg[D][WIDE_TPW];
+  u32x4 wreg[2][WIDE_TPW]; // two weight stages in flight in registers
   auto load_stage = [&](int slot, int s) { // unconditional, clamped: the counts in flight stay compile-time facts
 #pragma unroll
     for (int i = 0; i < WIDE_TPW; ++i) {
@@ -142,13 +141,13 @@ __global__ __launch_bounds__(WIDE_WAVES * 64) void k_gemm_wide(GemmArgs g, int32
 #pragma unroll
   for (int p2 = 0; p2 < NP2; ++p2) wsel[p2] = MODE == GEMM_SWIGLU ? p2 + P * half_sel : 2 * p2 + half_sel;
 
-  // D == 2: register slot of stage s is s & 1; at the top of iteration s the slots hold stages s + 1 and s + 2
+  // register slot of stage s is s & 1; at the top of iteration s the slots hold stages s + 1 and s + 2
   load_stage(0, 0);
 #pragma unroll
   for (int j = 0; j < WIDE_PA; ++j) issue_a(j, k0 + j);
-  if (D == 2) load_stage(D - 1, 1);
+  load_stage(1, 1);
   store_stage(0, 0, 0);
-  load_stage(0, D);
+  load_stage(0, 2);
   f32x16 acc[NP2][RP2];
 #pragma unroll
   for (int u = 0; u < NP2; ++u)
@@ -186,8 +185,8 @@ __global__ __launch_bounds__(WIDE_WAVES * 64) void k_gemm_wide(GemmArgs g, int32
         wc0 = wn0;
         wc1 = wn1;
       }
-      store_stage(D == 2 ? si ^ 1 : 0, si ^ 1, s + 1); // that buffer was last read before the previous barrier
-      load_stage(D == 2 ? si ^ 1 : 0, s + 1 + D);
+      store_stage(si ^ 1, si ^ 1, s + 1); // that buffer was last read before the previous barrier
+      load_stage(si ^ 1, s + 3);
       __syncthreads(); // uniform: every wave runs every stage
     }
   }
