@@ -16,11 +16,13 @@
 //
 // What bounds it (7B gate/up projection of 511 rows, 92 Gflop): with one row tile per wave the LDS set the pace
 // (every MFMA needs a 1 KiB tile read, the LDS delivers one per 8 clocks to the whole compute unit): 109 us.
-// With two or four row tiles per wave, 86-94 us = 1.0 PFLOP/s, and the same whether the weights come from memory
-// or from cache, whether the LDS reads run one or two tile pairs ahead or are left out, and with either MFMA
-// shape.  The matrix pipe is busy 45 % of that time and a compute unit receives 19-23 bytes per clock of global
-// loads, a third of what either can do alone: eight waves move in lockstep between the stage barriers, one
-// workgroup per compute unit, and nothing fills the time a wave spends in its waits.
+// With two or four row tiles per wave, 86-94 us = 1.0 PFLOP/s at a shader clock of 1.85 GHz (measured during the
+// launch), the matrix pipe 68 % busy.  That time did not move with the MFMA shape, the depth of the LDS read-ahead,
+// the place of the LDS hand-over in the stage, the stage size, a second workgroup per compute unit, or weight
+// stages brought in by direct global -> LDS loads; it follows the volume of global loads a compute unit issues
+// (-33 % without the weight loads, -15 % with one activation tile for all waves), 19-24 bytes per clock against
+// 60 for a loop of nothing but loads: the waves that load are the waves that must keep the matrix pipe fed, they
+// issue in order, and a load that waits for a slot in the memory pipe holds up the MFMAs behind it.
 //
 // Same packed weight layout, fragment-ordered activations and epilogues (plain store, RoPE + cache append,
 // SwiGLU) as the decode kernel.
