@@ -190,7 +190,7 @@ def test_prefill_crosses_chunk_boundaries():
 
 @pytest.mark.parametrize("shape_name,plen", [("tiny_bf16", 100), ("tiny_bf16", 150), ("tiny_gqa_bf16", 150),
                                              ("tiny_bf16", 513), ("tiny_gqa_bf16", 600), ("tiny_bf16", 700),
-                                             ("zoo_heads32", 300), ("tiny_gqa_bf16", 1100)])
+                                             ("zoo_heads32", 300), ("tiny_gqa_bf16", 1100), ("tiny_bf16", 2049)])
 def test_packed_prefill_cache_matches_oracle(shape_name, plen):
     """Packed bf16 models rotate and store queries, keys and values in the epilogue of the fused Q/K/V
     projection; the committed cache must hold the oracle's keys (read back through the interleaved feature
@@ -198,7 +198,7 @@ def test_packed_prefill_cache_matches_oracle(shape_name, plen):
     through the wide projection kernel in passes of up to 512 rows with attention per block of 128: the
     lengths cover one decode-path pass (99 rows), a ragged second block (149), exactly one full pass (512), a
     full pass plus a decode-path remainder (599 = 512 + 87), plus a ragged wide pass (699 = 512 + 187), a
-    single-layer model (only the Q/K/V projection runs) and two full passes (1099 = 512 + 512 + 75)."""
+    single-layer model (only the Q/K/V projection runs), two full passes (1099 = 512 + 512 + 75) and four (2048)."""
     require_gpu()
     say("packed prefill cache", shape_name, plen)
     sh = synth.SHAPES[shape_name]
@@ -362,6 +362,27 @@ def test_linear_bf16_packed_matches_oracle_matmul(n, K_, O_, splits):
     err = np.abs(y.cpu().numpy() - ref).max()
     say("max err", err)
     assert err < 2e-5 * np.sqrt(K_)                           # fp32 accumulation of K products of O(1/sqrt(K))
+
+
+def test_linear_row_limits():
+    """Packed weights take up to TR_PREFILL_ROWS rows (the prompt-ingestion kernel above TR_MAX_NODES), row-major
+    ones TR_MAX_NODES; one more is TR_EINVAL, on the host, before any launch."""
+    require_gpu()
+    ctx = tr.Context(16, 8, [-1], [-1], 1)
+    K_, O_ = 64, 32
+    w = synth.uniform_tensor((O_, K_), 0.1, seed=1, tensor_id=0, dtype=torch.bfloat16).cuda()
+    wp = tr.pack_weight(w)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    for n, packed, ok in ((512, True, True), (513, True, False), (128, False, True), (129, False, False)):
+        x = torch.zeros(n, K_, dtype=torch.bfloat16, device="cuda")
+        y = torch.zeros(n, O_, dtype=torch.float32, device="cuda")
+        if ok:
+            ctx.op_linear(x, wp if packed else w, y, ws, packed=packed, splits=1)
+        else:
+            with pytest.raises(tr.TRError) as e:
+                ctx.op_linear(x, wp if packed else w, y, ws, packed=packed, splits=1)
+            assert e.value.status == tr.TR_EINVAL
+    torch.cuda.synchronize()
 
 
 def test_linear_packed_every_planned_variant():
